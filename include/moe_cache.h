@@ -1,0 +1,218 @@
+/*
+ * moe_cache.h - C ABI of the MI355X MoE decode step with an offloaded-expert cache.
+ *
+ * One call to moe_layer_decode() runs one MoE block (paper section 2, Eq. 1-3)
+ * on a batch of tokens under expert offloading (section 2, "Expert Offloading
+ * Systems"; section 3.2):
+ *
+ *   router GEMV -> softmax / Top-K gating -> expert-cache lookup with on-demand
+ *   host->device fetch of missed experts -> SwiGLU expert FFN over the resident
+ *   experts -> weighted combine.
+ *
+ * Every step runs in HIP kernels on the device named in the config; the host
+ * only issues the asynchronous copies of missed experts.  There is no CPU
+ * fallback: without a usable GPU every entry point that needs one fails with
+ * MOE_ERR_HIP.
+ *
+ * Conventions
+ *   - All functions return MOE_OK (0) or a negative moe_status_t.  Nothing
+ *     throws, aborts or prints.  moe_last_error() returns a thread-local,
+ *     human-readable description of the last failure on the calling thread.
+ *   - "device" pointers are HIP device memory on the cache's device; "host"
+ *     pointers are ordinary host memory; "pinned host" is page-locked host
+ *     memory from hipHostMalloc (or torch pin_memory).  Borrowed pointers are
+ *     never freed by the library and must outlive the cache.
+ *   - Streams are passed as void* holding a hipStream_t (NULL = the null
+ *     stream).  Kernels of a call are enqueued on the caller's stream; expert
+ *     copies run on a stream the library owns.  A call returns once its work
+ *     is enqueued, after a short host wait for the miss list of that call.
+ *     Results are valid after the caller synchronises the stream.
+ *   - A cache object is not thread-safe; use one thread per cache.
+ */
+#ifndef MOE_CACHE_H
+#define MOE_CACHE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = -1,        /* null pointer, size out of range, bad enum value        */
+  MOE_ERR_CAPACITY_LT_TOPK = -2,   /* capacity < top_k: one token's experts would not fit    */
+  MOE_ERR_OUT_OF_MEMORY = -3,      /* host or device allocation failed                       */
+  MOE_ERR_HIP = -4,                /* a HIP runtime call failed (text in moe_last_error)     */
+  MOE_ERR_STAGING_EXHAUSTED = -5,  /* a batched call needed more spare expert buffers than
+                                      `staging_buffers`; the cache state is left unchanged   */
+  MOE_ERR_UNSUPPORTED = -6,        /* shape / layout combination without a kernel            */
+  MOE_ERR_TIMEOUT = -7             /* the device did not report the miss list in time        */
+} moe_status_t;
+
+enum { MOE_DTYPE_FP32 = 0, MOE_DTYPE_BF16 = 1 };
+enum { MOE_POLICY_LRU = 0, MOE_POLICY_GAMMA = 1 };
+enum { MOE_LAYOUT_ROWMAJOR = 0, MOE_LAYOUT_TILED = 1 };
+
+typedef struct moe_cache moe_cache_t; /* opaque; owned by the library */
+
+/*
+ * Shape and policy of a layer stack.  Notation follows the paper: E experts
+ * per layer, K active per token, hidden width d, intermediate width d_ff,
+ * cache capacity C resident experts per layer.
+ */
+typedef struct {
+  int32_t n_layers;        /* L >= 1                                                        */
+  int32_t n_experts;       /* E, routed experts per layer, 1..1024                          */
+  int32_t n_shared;        /* always-resident experts added with weight 1 (0 = none)        */
+  int32_t top_k;           /* K, 1..min(E,64)                                               */
+  int32_t d_model;         /* d                                                             */
+  int32_t d_ff;            /* intermediate width of one expert                              */
+  int32_t capacity;        /* C, K <= C; values above E are clamped to E                    */
+  int32_t dtype;           /* MOE_DTYPE_*: storage type of weights, x and y                 */
+  int32_t norm_topk;       /* 1: gate weights renormalised over the K selected (sum to 1);
+                              0: Eq. 2 as printed (softmax over all E, not renormalised)    */
+  int32_t policy;          /* MOE_POLICY_LRU: least recently used (gamma -> 0+ limit of
+                              Definition C.1); MOE_POLICY_GAMMA: discounted request counts
+                              of Definition C.1 with `gamma` (gamma = 1 is LFU)             */
+  int32_t max_batch;       /* largest `batch` a call may pass, >= 1                         */
+  int32_t staging_buffers; /* spare expert buffers per layer beyond C, >= 0.  Needed only
+                              when one call can evict an expert that an earlier token of
+                              the same call hit (batch * K > C); batch 1 needs none         */
+  int32_t device_id;       /* HIP device ordinal; -1 = the calling thread's current device  */
+  int32_t trace_capacity;  /* lookup records kept per layer (0 = tracing off)               */
+  int32_t pool_layout;     /* MOE_LAYOUT_*: layout of every expert block (see below)        */
+  int32_t reserved;        /* must be 0                                                     */
+  double gamma;            /* decay of MOE_POLICY_GAMMA, in [0,1]; ignored for LRU          */
+} moe_cache_config_t;
+
+/*
+ * Parameters.  All BORROWED for the life of the cache.
+ *
+ * An expert block holds the three matrices of Eq. 3 for one expert,
+ * expert_bytes = 3 * d * d_ff * sizeof(dtype) bytes:
+ *   MOE_LAYOUT_ROWMAJOR  W_g [d_ff][d] | W_u [d_ff][d] | W_d [d][d_ff], row-major.
+ *   MOE_LAYOUT_TILED     bf16 only; the same values permuted into the order the
+ *                        streaming kernels read them (written by moe_pack_expert).
+ */
+typedef struct {
+  const void* router_w;    /* device, [L][E][d] row-major, dtype                            */
+  const void* expert_pool; /* pinned host, [L][E] expert blocks                             */
+  const void* shared_w;    /* device, [L][n_shared] expert blocks; NULL iff n_shared == 0   */
+} moe_weights_t;
+
+typedef struct {
+  uint64_t lookups;   /* (token, selected expert) pairs looked up by moe_layer_decode       */
+  uint64_t hits;      /* lookups that found the expert resident                             */
+  uint64_t misses;    /* lookups that did not; each one is one host->device expert copy     */
+  uint64_t evictions; /* resident experts dropped to make room (decode and prefill_pins)    */
+  uint64_t pin_loads; /* expert copies issued by moe_cache_prefill_pins                     */
+  uint64_t bytes_h2d; /* (misses + pin_loads) * expert_bytes                                */
+} moe_cache_stats_t;
+
+/* One lookup, in the order the lookups were made. */
+typedef struct {
+  int32_t token;   /* row of the batch the lookup belongs to                                */
+  int32_t expert;  /* expert id                                                             */
+  int32_t hit;     /* 1 = resident, 0 = fetched                                             */
+  int32_t evicted; /* expert dropped to make room, -1 if none                               */
+} moe_trace_rec_t;
+
+/* Device-side timing collected while profiling is on (moe_cache_set_profiling). */
+typedef struct {
+  uint64_t ffn_launches; /* decode calls whose expert-FFN kernels were timed                */
+  double ffn_gate_up_ms; /* summed duration of the gate/up (first) FFN kernel               */
+  double ffn_down_ms;    /* summed duration of the down-projection kernel                   */
+  double route_ms;       /* summed duration of the router + cache-lookup kernels            */
+  uint64_t copies;       /* expert copies timed                                             */
+  uint64_t copy_bytes;   /* bytes moved by them                                             */
+  double copy_ms;        /* summed duration of the copy batches on the copy stream          */
+} moe_timing_t;
+
+/* Bytes of one expert block for the given shape; 0 if the arguments are invalid. */
+uint64_t moe_expert_bytes(int32_t d_model, int32_t d_ff, int32_t dtype);
+
+/*
+ * Host-side helper: permute one bf16 expert from MOE_LAYOUT_ROWMAJOR (src, host)
+ * into MOE_LAYOUT_TILED (dst, host; may be pinned).  Pure data movement.
+ * Requires d_model % 32 == 0 and d_ff % 32 == 0.  src and dst must not overlap.
+ */
+int moe_pack_expert(const void* src_rowmajor, void* dst_tiled, int32_t d_model, int32_t d_ff);
+
+/*
+ * Create a cache for a layer stack: allocates L * (C + staging_buffers) expert
+ * buffers on the device, the per-layer cache tables, scratch for max_batch
+ * tokens and a copy stream.  All caches start empty.
+ * Errors: INVALID_ARG, CAPACITY_LT_TOPK, UNSUPPORTED (e.g. tiled layout with
+ * fp32, widths not multiples of 32), OUT_OF_MEMORY, HIP.  *out is NULL on error.
+ */
+int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights, moe_cache_t** out);
+
+/* Waits for outstanding work of the cache, then frees everything it owns. */
+int moe_cache_destroy(moe_cache_t* cache);
+
+/*
+ * Empty the cache of one layer (layer = -1: all layers): no expert resident,
+ * recency and counts cleared.  Statistics and the trace are kept unless
+ * clear_stats != 0.  Ordered after previously enqueued work on `hip_stream`.
+ */
+int moe_cache_reset(moe_cache_t* cache, int32_t layer, int32_t clear_stats, void* hip_stream);
+
+/*
+ * Preload experts before generation (section 3.2: the prefetch set
+ * Top-C of the predictor's scores is loaded into the cache before decoding).
+ * Equivalent to n lookups in list order that are counted as pin_loads rather
+ * than hits or misses; entries already resident are only refreshed; loaded
+ * experts remain evictable.  expert_ids: host, n distinct ids in [0,E), n <= C.
+ * The copies run on the library's copy stream; later calls on any stream are
+ * ordered after them.
+ */
+int moe_cache_prefill_pins(moe_cache_t* cache, int32_t layer, const int32_t* expert_ids,
+                           int32_t n, void* hip_stream);
+
+/*
+ * One MoE block on `batch` tokens (Eq. 1-3 with the offloading runtime).
+ *   x_dev          device, [batch][d], dtype; read only
+ *   logit_bias_dev device, [batch][E] fp32 added to the router logits; may be NULL
+ *   y_dev          device, [batch][d], dtype; written
+ *   topk_idx_dev   device, [batch][K] int32, selected experts in ascending id; may be NULL
+ *   topk_w_dev     device, [batch][K] fp32 gate weights aligned with topk_idx; may be NULL
+ * Tokens are looked up in row order and, within a token, in ascending expert id.
+ * Errors: INVALID_ARG (null x/y, batch < 1 or > max_batch, layer out of range),
+ * STAGING_EXHAUSTED, HIP, TIMEOUT.
+ */
+int moe_layer_decode(moe_cache_t* cache, int32_t layer, const void* x_dev,
+                     const float* logit_bias_dev, int32_t batch, void* y_dev,
+                     int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
+
+/* Counters of one layer (layer = -1: summed over layers).  Host-side, no device wait. */
+int moe_cache_stats(const moe_cache_t* cache, int32_t layer, moe_cache_stats_t* out);
+
+/*
+ * Copy up to `max_records` lookup records of one layer, oldest first, into
+ * host_out (host).  *n_out = records copied; *n_total (may be NULL) = records
+ * produced since the last clear, which exceeds trace_capacity if it overflowed.
+ * Waits for the layer's enqueued work.
+ */
+int moe_cache_read_trace(moe_cache_t* cache, int32_t layer, moe_trace_rec_t* host_out,
+                         int64_t max_records, int64_t* n_out, int64_t* n_total);
+
+/* Expert ids resident in one layer, ascending, into host_out[capacity]; *n_out = count. */
+int moe_cache_resident(moe_cache_t* cache, int32_t layer, int32_t* host_out, int32_t* n_out);
+
+/* Turn per-kernel HIP-event timing on (1) or off (0); off by default. */
+int moe_cache_set_profiling(moe_cache_t* cache, int32_t enabled);
+
+/* Read and optionally clear the timing sums; waits for the timed work. */
+int moe_cache_timing(moe_cache_t* cache, moe_timing_t* out, int32_t clear);
+
+/* Text of the last error on this thread ("" if none). */
+const char* moe_last_error(void);
+
+/* Library version string. */
+const char* moe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_CACHE_H */

@@ -1,0 +1,652 @@
+// Host runtime behind the C ABI of include/moe_cache.h: owns the device expert
+// buffers, the per-layer cache tables, the copy stream and the per-call
+// orchestration of one MoE block (paper section 2, Eq. 1-3, under the
+// offloading runtime of section 3.2).
+//
+// Order of one moe_layer_decode() call on the caller's stream:
+//   route kernel -> cache kernel -> [expert FFN over the groups whose expert was
+//   already resident] -> (host reads the miss list the cache kernel left in
+//   pinned memory; for each miss: hipMemcpyAsync pinned pool -> device buffer on
+//   the copy stream; the caller's stream waits for the copies) -> [expert FFN
+//   over the fetched groups] -> combine.
+// The FFN over resident experts is enqueued before the host looks at the miss
+// list, so the host round trip and the PCIe copies overlap that compute, as
+// Eq. 4's additive model (compute + N_miss * transfer) is the worst case.
+#include <algorithm>
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "moe_internal.hpp"
+
+using namespace moe;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIPCHK(expr)                                                                        \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return fail(MOE_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr int kProfSlots = 512;
+
+struct ProfSlot {
+  hipEvent_t e0 = nullptr, e1 = nullptr, e2 = nullptr, e3 = nullptr;  // route start, ffn start, ffn mid, ffn end
+  bool used = false;
+  bool mixed = false;  // the call also fetched experts: its FFN span includes copy waits, not added to the sums
+};
+struct CopySlot {
+  hipEvent_t c0 = nullptr, c1 = nullptr;
+  uint64_t bytes = 0;
+  int n = 0;
+  bool used = false;
+};
+
+}  // namespace
+
+struct moe_cache {
+  moe_cache_config_t cfg{};
+  moe_weights_t w{};
+  int device = 0;
+  int C = 0, P = 0, KS = 0, G = 0;
+  uint64_t expert_bytes = 0;
+  size_t elem = 2;
+
+  char* buffers = nullptr;        // [L][P] expert blocks
+  char* table_mem = nullptr;      // all LayerState arrays
+  std::vector<LayerState> layers;
+  CallTables t{};
+  char* call_mem = nullptr;
+  void* h = nullptr;
+  float* o = nullptr;
+
+  char* host_mem = nullptr;       // pinned: mailbox | pin ids | miss list
+  Mailbox* mailbox = nullptr;
+  int32_t* pin_ids = nullptr;
+  MissEntry* miss_list = nullptr;
+  int max_miss = 0;
+
+  hipStream_t copy_stream = nullptr;
+  hipEvent_t ev_mail = nullptr, ev_copy = nullptr, ev_order = nullptr;
+  uint32_t seq = 0;
+  bool copies_pending = false;    // copies issued that no stream has been ordered after yet
+
+  std::vector<moe_cache_stats_t> stats;
+
+  bool profiling = false;
+  std::vector<ProfSlot> prof;
+  std::vector<CopySlot> cprof;
+  int prof_head = 0, cprof_head = 0;
+  moe_timing_t timing{};
+};
+
+namespace {
+
+struct DeviceGuard {
+  int prev = -1;
+  bool switched = false;
+  hipError_t enter(int dev) {
+    hipError_t e = hipGetDevice(&prev);
+    if (e != hipSuccess) return e;
+    if (prev != dev) {
+      e = hipSetDevice(dev);
+      switched = e == hipSuccess;
+    }
+    return e;
+  }
+  ~DeviceGuard() {
+    if (switched) (void)hipSetDevice(prev);
+  }
+};
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+int validate(const moe_cache_config_t* c, const moe_weights_t* w) {
+  if (!c || !w) return fail(MOE_ERR_INVALID_ARG, "null config or weights");
+  if (c->n_layers < 1) return fail(MOE_ERR_INVALID_ARG, "n_layers must be >= 1");
+  if (c->n_experts < 1 || c->n_experts > 1024) return fail(MOE_ERR_INVALID_ARG, "n_experts must be in 1..1024");
+  if (c->n_shared < 0 || c->n_shared > 64) return fail(MOE_ERR_INVALID_ARG, "n_shared must be in 0..64");
+  if (c->top_k < 1 || c->top_k > c->n_experts || c->top_k > 64)
+    return fail(MOE_ERR_INVALID_ARG, "top_k must be in 1..min(n_experts,64)");
+  if (c->d_model < 1 || c->d_ff < 1) return fail(MOE_ERR_INVALID_ARG, "d_model and d_ff must be positive");
+  if (c->dtype != MOE_DTYPE_FP32 && c->dtype != MOE_DTYPE_BF16) return fail(MOE_ERR_INVALID_ARG, "unknown dtype");
+  if (c->norm_topk != 0 && c->norm_topk != 1) return fail(MOE_ERR_INVALID_ARG, "norm_topk must be 0 or 1");
+  if (c->policy != MOE_POLICY_LRU && c->policy != MOE_POLICY_GAMMA) return fail(MOE_ERR_INVALID_ARG, "unknown policy");
+  if (c->policy == MOE_POLICY_GAMMA && !(c->gamma >= 0.0 && c->gamma <= 1.0))
+    return fail(MOE_ERR_INVALID_ARG, "gamma must be in [0,1]");
+  if (c->max_batch < 1 || c->max_batch > (1 << 20)) return fail(MOE_ERR_INVALID_ARG, "max_batch out of range");
+  if (c->staging_buffers < 0 || c->staging_buffers > 1024) return fail(MOE_ERR_INVALID_ARG, "staging_buffers out of range");
+  if (c->trace_capacity < 0) return fail(MOE_ERR_INVALID_ARG, "trace_capacity must be >= 0");
+  if (c->pool_layout != MOE_LAYOUT_ROWMAJOR && c->pool_layout != MOE_LAYOUT_TILED)
+    return fail(MOE_ERR_INVALID_ARG, "unknown pool_layout");
+  if (c->reserved != 0) return fail(MOE_ERR_INVALID_ARG, "reserved must be 0");
+  if (c->capacity < 1) return fail(MOE_ERR_INVALID_ARG, "capacity must be >= 1");
+  if (c->capacity < c->top_k)
+    return fail(MOE_ERR_CAPACITY_LT_TOPK, "capacity %d < top_k %d: one token's experts would not fit", c->capacity,
+                c->top_k);
+  if (!w->router_w || !w->expert_pool) return fail(MOE_ERR_INVALID_ARG, "router_w and expert_pool must not be null");
+  if ((c->n_shared > 0) != (w->shared_w != nullptr))
+    return fail(MOE_ERR_INVALID_ARG, "shared_w must be given exactly when n_shared > 0");
+  const int vec = c->dtype == MOE_DTYPE_FP32 ? 4 : 8;
+  if (c->d_model % vec != 0)
+    return fail(MOE_ERR_UNSUPPORTED, "d_model must be a multiple of %d for this dtype", vec);
+  if (c->pool_layout == MOE_LAYOUT_TILED) {
+    if (c->dtype != MOE_DTYPE_BF16) return fail(MOE_ERR_UNSUPPORTED, "the tiled layout is bf16 only");
+    if (c->d_model % 32 != 0 || c->d_ff % 32 != 0)
+      return fail(MOE_ERR_UNSUPPORTED, "the tiled layout needs d_model and d_ff to be multiples of 32");
+  }
+  if ((reinterpret_cast<uintptr_t>(w->router_w) & 15) || (reinterpret_cast<uintptr_t>(w->expert_pool) & 15) ||
+      (reinterpret_cast<uintptr_t>(w->shared_w) & 15))
+    return fail(MOE_ERR_INVALID_ARG, "weight pointers must be 16-byte aligned");
+  return MOE_OK;
+}
+
+void free_all(moe_cache* c) {
+  if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
+  for (auto& p : c->prof) {
+    if (p.e0) (void)hipEventDestroy(p.e0);
+    if (p.e1) (void)hipEventDestroy(p.e1);
+    if (p.e2) (void)hipEventDestroy(p.e2);
+    if (p.e3) (void)hipEventDestroy(p.e3);
+  }
+  for (auto& p : c->cprof) {
+    if (p.c0) (void)hipEventDestroy(p.c0);
+    if (p.c1) (void)hipEventDestroy(p.c1);
+  }
+  if (c->ev_mail) (void)hipEventDestroy(c->ev_mail);
+  if (c->ev_copy) (void)hipEventDestroy(c->ev_copy);
+  if (c->ev_order) (void)hipEventDestroy(c->ev_order);
+  if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  if (c->buffers) (void)hipFree(c->buffers);
+  if (c->table_mem) (void)hipFree(c->table_mem);
+  if (c->call_mem) (void)hipFree(c->call_mem);
+  if (c->h) (void)hipFree(c->h);
+  if (c->o) (void)hipFree(c->o);
+  if (c->host_mem) (void)hipHostFree(c->host_mem);
+  delete c;
+}
+
+// Wait until the cache kernel of call `seq` has filled the mailbox.
+int wait_mailbox(moe_cache* c, hipStream_t s, uint32_t seq) {
+  HIPCHK(hipEventRecord(c->ev_mail, s));
+  HIPCHK(hipEventSynchronize(c->ev_mail));
+  const uint32_t got = __atomic_load_n(&c->mailbox->seq, __ATOMIC_ACQUIRE);
+  if (got != seq) return fail(MOE_ERR_TIMEOUT, "miss list of call %u not delivered (mailbox holds %u)", seq, got);
+  return MOE_OK;
+}
+
+// Issue the expert copies of the current mailbox on the copy stream.
+int issue_copies(moe_cache* c, int layer, int n) {
+  const size_t eb = c->expert_bytes;
+  const char* pool = static_cast<const char*>(c->w.expert_pool) + (size_t)layer * c->cfg.n_experts * eb;
+  char* bufs = c->buffers + (size_t)layer * c->P * eb;
+  CopySlot* cs = nullptr;
+  if (c->profiling) {
+    cs = &c->cprof[c->cprof_head];
+    if (cs->used) {
+      HIPCHK(hipEventSynchronize(cs->c1));
+      float ms = 0.f;
+      HIPCHK(hipEventElapsedTime(&ms, cs->c0, cs->c1));
+      c->timing.copy_ms += ms;
+      c->timing.copies += cs->n;
+      c->timing.copy_bytes += cs->bytes;
+      cs->used = false;
+    }
+    HIPCHK(hipEventRecord(cs->c0, c->copy_stream));
+  }
+  for (int i = 0; i < n; ++i) {
+    const MissEntry m = c->miss_list[i];
+    if (m.expert < 0 || m.expert >= c->cfg.n_experts || m.buffer < 0 || m.buffer >= c->P)
+      return fail(MOE_ERR_HIP, "corrupt miss list entry (%d,%d)", m.expert, m.buffer);
+    HIPCHK(hipMemcpyAsync(bufs + (size_t)m.buffer * eb, pool + (size_t)m.expert * eb, eb, hipMemcpyHostToDevice,
+                          c->copy_stream));
+  }
+  if (cs) {
+    HIPCHK(hipEventRecord(cs->c1, c->copy_stream));
+    cs->bytes = (uint64_t)n * eb;
+    cs->n = n;
+    cs->used = true;
+    c->cprof_head = (c->cprof_head + 1) % kProfSlots;
+  }
+  HIPCHK(hipEventRecord(c->ev_copy, c->copy_stream));
+  c->copies_pending = true;
+  return MOE_OK;
+}
+
+int drain_prof_slot(moe_cache* c, ProfSlot& p) {
+  if (!p.used) return MOE_OK;
+  HIPCHK(hipEventSynchronize(p.e3));
+  float a = 0.f, b = 0.f, r = 0.f;
+  HIPCHK(hipEventElapsedTime(&r, p.e0, p.e1));
+  HIPCHK(hipEventElapsedTime(&a, p.e1, p.e2));
+  HIPCHK(hipEventElapsedTime(&b, p.e2, p.e3));
+  c->timing.route_ms += r;
+  if (!p.mixed) {
+    c->timing.ffn_gate_up_ms += a;
+    c->timing.ffn_down_ms += b;
+    c->timing.ffn_launches += 1;
+  }
+  p.used = false;
+  return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_last_error(void) { return g_err; }
+const char* moe_version(void) { return "moe_cache 0.1 (gfx950)"; }
+
+uint64_t moe_expert_bytes(int32_t d_model, int32_t d_ff, int32_t dtype) {
+  if (d_model < 1 || d_ff < 1 || (dtype != MOE_DTYPE_FP32 && dtype != MOE_DTYPE_BF16)) return 0;
+  return (uint64_t)3 * (uint64_t)d_model * (uint64_t)d_ff * (dtype == MOE_DTYPE_FP32 ? 4u : 2u);
+}
+
+int moe_pack_expert(const void* src_rowmajor, void* dst_tiled, int32_t d, int32_t f) {
+  if (!src_rowmajor || !dst_tiled) return fail(MOE_ERR_INVALID_ARG, "null pointer");
+  if (d < 32 || f < 32 || d % 32 != 0 || f % 32 != 0)
+    return fail(MOE_ERR_UNSUPPORTED, "d_model and d_ff must be positive multiples of 32");
+  const uint16_t* src = static_cast<const uint16_t*>(src_rowmajor);
+  uint16_t* dst = static_cast<uint16_t*>(dst_tiled);
+  const uint16_t* wg = src;
+  const uint16_t* wu = src + (size_t)f * d;
+  const uint16_t* wd = src + (size_t)2 * f * d;
+  // gate/up section: [f/16][d/32][2][64][8]
+  const int nkb_d = d / 32, nkb_f = f / 32;
+  for (int ft = 0; ft < f / 16; ++ft)
+    for (int kb = 0; kb < nkb_d; ++kb)
+      for (int m = 0; m < 2; ++m) {
+        const uint16_t* w = m == 0 ? wg : wu;
+        uint16_t* out = dst + (((size_t)ft * nkb_d + kb) * 2 + m) * 512;
+        for (int l = 0; l < 64; ++l)
+          memcpy(out + l * 8, w + (size_t)(ft * 16 + (l & 15)) * d + kb * 32 + (l >> 4) * 8, 16);
+      }
+  // down section: [d/16][f/32][64][8]
+  uint16_t* dsec = dst + (size_t)2 * f * d;
+  for (int dt = 0; dt < d / 16; ++dt)
+    for (int kb = 0; kb < nkb_f; ++kb) {
+      uint16_t* out = dsec + ((size_t)dt * nkb_f + kb) * 512;
+      for (int l = 0; l < 64; ++l)
+        memcpy(out + l * 8, wd + (size_t)(dt * 16 + (l & 15)) * f + kb * 32 + (l >> 4) * 8, 16);
+    }
+  return MOE_OK;
+}
+
+int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights, moe_cache_t** out) {
+  if (out) *out = nullptr;
+  if (!out) return fail(MOE_ERR_INVALID_ARG, "out must not be null");
+  int rc = validate(cfg, weights);
+  if (rc != MOE_OK) return rc;
+
+  int n_dev = 0;
+  hipError_t he = hipGetDeviceCount(&n_dev);
+  if (he != hipSuccess || n_dev < 1) {
+    (void)hipGetLastError();
+    return fail(MOE_ERR_HIP, "no HIP device available (%s)", he == hipSuccess ? "device count 0" : hipGetErrorString(he));
+  }
+  int dev = cfg->device_id;
+  if (dev < 0) HIPCHK(hipGetDevice(&dev));
+  if (dev >= n_dev) return fail(MOE_ERR_INVALID_ARG, "device_id %d out of range (%d devices)", dev, n_dev);
+  DeviceGuard guard;
+  HIPCHK(guard.enter(dev));
+
+  moe_cache* c = new (std::nothrow) moe_cache();
+  if (!c) return fail(MOE_ERR_OUT_OF_MEMORY, "host allocation failed");
+  c->cfg = *cfg;
+  c->w = *weights;
+  c->device = dev;
+  const int L = cfg->n_layers, E = cfg->n_experts, K = cfg->top_k;
+  c->C = std::min(cfg->capacity, E);
+  c->P = c->C + cfg->staging_buffers;
+  c->KS = K + cfg->n_shared;
+  c->expert_bytes = moe_expert_bytes(cfg->d_model, cfg->d_ff, cfg->dtype);
+  c->elem = cfg->dtype == MOE_DTYPE_FP32 ? 4 : 2;
+  const int C = c->C, P = c->P, KS = c->KS, Bm = cfg->max_batch;
+  const size_t NP = (size_t)Bm * KS;
+  c->G = (int)std::min<size_t>((size_t)Bm * K, (size_t)P) + cfg->n_shared;
+  c->max_miss = (int)std::max<size_t>((size_t)Bm * K, (size_t)C);
+  c->stats.assign(L, moe_cache_stats_t{});
+
+  CacheCallArgs probe{};
+  probe.E = E; probe.C = C; probe.P = P; probe.n_shared = cfg->n_shared;
+  if (cache_kernel_lds_bytes(probe) > 60 * 1024) {
+    delete c;
+    return fail(MOE_ERR_UNSUPPORTED, "cache table of this size does not fit in LDS");
+  }
+
+#define CREATE_CHK(expr, code)                                                      \
+  do {                                                                              \
+    hipError_t e_ = (expr);                                                         \
+    if (e_ != hipSuccess) {                                                         \
+      (void)hipGetLastError();                                                      \
+      free_all(c);                                                                  \
+      return fail(e_ == hipErrorOutOfMemory ? MOE_ERR_OUT_OF_MEMORY : (code), "%s: %s", #expr, \
+                  hipGetErrorString(e_));                                           \
+    }                                                                               \
+  } while (0)
+
+  CREATE_CHK(hipMalloc(&c->buffers, (size_t)L * P * c->expert_bytes), MOE_ERR_HIP);
+
+  // ---- per-layer tables ----
+  size_t per_layer = 0;
+  const size_t o_tick = per_layer; per_layer += align_up((size_t)C * 8, 16);
+  const size_t o_score = per_layer; per_layer += align_up((size_t)E * 8, 16);
+  const size_t o_scal = per_layer; per_layer += align_up((size_t)SC_COUNT * 8, 16);
+  const size_t o_ein = per_layer; per_layer += align_up((size_t)C * 4, 16);
+  const size_t o_bos = per_layer; per_layer += align_up((size_t)C * 4, 16);
+  const size_t o_sof = per_layer; per_layer += align_up((size_t)E * 4, 16);
+  const size_t o_free = per_layer; per_layer += align_up((size_t)P * 4, 16);
+  const size_t o_zom = per_layer; per_layer += align_up((size_t)P * 4, 16);
+  const size_t o_used = per_layer; per_layer += align_up((size_t)P * 4, 16);
+  const size_t o_trace = per_layer; per_layer += align_up((size_t)cfg->trace_capacity * sizeof(moe_trace_rec_t), 16);
+  CREATE_CHK(hipMalloc(&c->table_mem, per_layer * L), MOE_ERR_HIP);
+  CREATE_CHK(hipMemset(c->table_mem, 0, per_layer * L), MOE_ERR_HIP);
+  c->layers.resize(L);
+  for (int l = 0; l < L; ++l) {
+    char* b = c->table_mem + per_layer * l;
+    LayerState& s = c->layers[l];
+    s.tick = reinterpret_cast<uint64_t*>(b + o_tick);
+    s.score = reinterpret_cast<double*>(b + o_score);
+    s.scalars = reinterpret_cast<int64_t*>(b + o_scal);
+    s.expert_in = reinterpret_cast<int32_t*>(b + o_ein);
+    s.buf_of_slot = reinterpret_cast<int32_t*>(b + o_bos);
+    s.slot_of = reinterpret_cast<int32_t*>(b + o_sof);
+    s.free_buf = reinterpret_cast<int32_t*>(b + o_free);
+    s.zombie = reinterpret_cast<int32_t*>(b + o_zom);
+    s.used_stamp = reinterpret_cast<uint32_t*>(b + o_used);
+    s.trace = cfg->trace_capacity > 0 ? reinterpret_cast<moe_trace_rec_t*>(b + o_trace) : nullptr;
+  }
+
+  // ---- per-call scratch ----
+  size_t cm = 0;
+  const size_t o_idx = cm; cm += align_up((size_t)Bm * K * 4, 16);
+  const size_t o_wp = cm; cm += align_up(NP * 4, 16);
+  const size_t o_pb = cm; cm += align_up(NP * 4, 16);
+  const size_t o_sp = cm; cm += align_up(NP * 4, 16);
+  const size_t o_po = cm; cm += align_up(NP * 4, 16);
+  const size_t o_gb = cm; cm += align_up((size_t)c->G * 4, 16);
+  const size_t o_gbeg = cm; cm += align_up((size_t)c->G * 4, 16);
+  const size_t o_gc = cm; cm += align_up((size_t)c->G * 4, 16);
+  const size_t o_gm = cm; cm += align_up((size_t)c->G * 4, 16);
+  const size_t o_ng = cm; cm += 16;
+  CREATE_CHK(hipMalloc(&c->call_mem, cm), MOE_ERR_HIP);
+  CREATE_CHK(hipMemset(c->call_mem, 0, cm), MOE_ERR_HIP);
+  c->t.idx = reinterpret_cast<int32_t*>(c->call_mem + o_idx);
+  c->t.wpair = reinterpret_cast<float*>(c->call_mem + o_wp);
+  c->t.pair_buf = reinterpret_cast<int32_t*>(c->call_mem + o_pb);
+  c->t.sorted_pair = reinterpret_cast<int32_t*>(c->call_mem + o_sp);
+  c->t.pos_of = reinterpret_cast<int32_t*>(c->call_mem + o_po);
+  c->t.grp_buf = reinterpret_cast<int32_t*>(c->call_mem + o_gb);
+  c->t.grp_begin = reinterpret_cast<int32_t*>(c->call_mem + o_gbeg);
+  c->t.grp_count = reinterpret_cast<int32_t*>(c->call_mem + o_gc);
+  c->t.grp_miss = reinterpret_cast<int32_t*>(c->call_mem + o_gm);
+  c->t.n_groups = reinterpret_cast<int32_t*>(c->call_mem + o_ng);
+  CREATE_CHK(hipMalloc(&c->h, NP * cfg->d_ff * 4), MOE_ERR_HIP);
+  CREATE_CHK(hipMalloc(reinterpret_cast<void**>(&c->o), NP * cfg->d_model * 4), MOE_ERR_HIP);
+
+  // ---- pinned mailbox ----
+  const size_t hm = align_up(sizeof(Mailbox), 64) + align_up((size_t)C * 4, 64) + (size_t)c->max_miss * sizeof(MissEntry);
+  CREATE_CHK(hipHostMalloc(reinterpret_cast<void**>(&c->host_mem), hm, hipHostMallocMapped | hipHostMallocCoherent),
+             MOE_ERR_OUT_OF_MEMORY);
+  memset(c->host_mem, 0, hm);
+  c->mailbox = reinterpret_cast<Mailbox*>(c->host_mem);
+  c->pin_ids = reinterpret_cast<int32_t*>(c->host_mem + align_up(sizeof(Mailbox), 64));
+  c->miss_list = reinterpret_cast<MissEntry*>(c->host_mem + align_up(sizeof(Mailbox), 64) + align_up((size_t)C * 4, 64));
+
+  CREATE_CHK(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking), MOE_ERR_HIP);
+  CREATE_CHK(hipEventCreateWithFlags(&c->ev_mail, hipEventDisableTiming), MOE_ERR_HIP);
+  CREATE_CHK(hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming), MOE_ERR_HIP);
+  CREATE_CHK(hipEventCreateWithFlags(&c->ev_order, hipEventDisableTiming), MOE_ERR_HIP);
+
+  for (int l = 0; l < L; ++l) CREATE_CHK(launch_reset(nullptr, c->layers[l], E, C, P, 1), MOE_ERR_HIP);
+  CREATE_CHK(hipStreamSynchronize(nullptr), MOE_ERR_HIP);
+#undef CREATE_CHK
+  *out = c;
+  return MOE_OK;
+}
+
+int moe_cache_destroy(moe_cache_t* c) {
+  if (!c) return MOE_OK;
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  (void)hipDeviceSynchronize();
+  free_all(c);
+  return MOE_OK;
+}
+
+int moe_cache_reset(moe_cache_t* c, int32_t layer, int32_t clear_stats, void* hip_stream) {
+  if (!c) return fail(MOE_ERR_INVALID_ARG, "null cache");
+  if (layer < -1 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? c->cfg.n_layers : layer + 1;
+  for (int l = l0; l < l1; ++l) {
+    HIPCHK(launch_reset(s, c->layers[l], c->cfg.n_experts, c->C, c->P, clear_stats ? 1 : 0));
+    if (clear_stats) c->stats[l] = moe_cache_stats_t{};
+  }
+  return MOE_OK;
+}
+
+int moe_cache_prefill_pins(moe_cache_t* c, int32_t layer, const int32_t* expert_ids, int32_t n, void* hip_stream) {
+  if (!c) return fail(MOE_ERR_INVALID_ARG, "null cache");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  if (n < 0 || n > c->C) return fail(MOE_ERR_INVALID_ARG, "n = %d pins exceed the capacity %d", n, c->C);
+  if (n == 0) return MOE_OK;
+  if (!expert_ids) return fail(MOE_ERR_INVALID_ARG, "expert_ids must not be null");
+  for (int i = 0; i < n; ++i) {
+    if (expert_ids[i] < 0 || expert_ids[i] >= c->cfg.n_experts)
+      return fail(MOE_ERR_INVALID_ARG, "pin id %d out of range", expert_ids[i]);
+    for (int j = 0; j < i; ++j)
+      if (expert_ids[j] == expert_ids[i]) return fail(MOE_ERR_INVALID_ARG, "duplicate pin id %d", expert_ids[i]);
+  }
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  memcpy(c->pin_ids, expert_ids, (size_t)n * 4);
+
+  CacheCallArgs a{};
+  a.mode = 1; a.B = 1; a.K = n; a.KS = n; a.E = c->cfg.n_experts; a.C = c->C; a.P = c->P;
+  a.n_shared = c->cfg.n_shared; a.policy = c->cfg.policy; a.gamma = c->cfg.gamma;
+  a.trace_cap = c->cfg.trace_capacity; a.seq = ++c->seq; a.pin_ids = c->pin_ids;
+  a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
+  if (c->copies_pending) { HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0)); c->copies_pending = false; }
+  HIPCHK(launch_cache(s, c->layers[layer], c->t, a));
+  int rc = wait_mailbox(c, s, a.seq);
+  if (rc != MOE_OK) return rc;
+  const Mailbox mb = *c->mailbox;
+  if (mb.status != MOE_OK) return fail(mb.status, "prefill_pins ran out of expert buffers");
+  if (mb.n_miss > 0) {
+    rc = issue_copies(c, layer, mb.n_miss);
+    if (rc != MOE_OK) return rc;
+    HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0));
+    c->copies_pending = false;
+  }
+  moe_cache_stats_t& st = c->stats[layer];
+  st.pin_loads += (uint64_t)mb.n_miss;
+  st.evictions += (uint64_t)mb.n_evict;
+  st.bytes_h2d += (uint64_t)mb.n_miss * c->expert_bytes;
+  return MOE_OK;
+}
+
+int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const float* logit_bias_dev, int32_t batch,
+                     void* y_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
+  if (!c) return fail(MOE_ERR_INVALID_ARG, "null cache");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  if (!x_dev || !y_dev) return fail(MOE_ERR_INVALID_ARG, "x_dev and y_dev must not be null");
+  if (batch < 1 || batch > c->cfg.max_batch)
+    return fail(MOE_ERR_INVALID_ARG, "batch %d outside 1..max_batch=%d", batch, c->cfg.max_batch);
+  if (reinterpret_cast<uintptr_t>(x_dev) & 15) return fail(MOE_ERR_INVALID_ARG, "x_dev must be 16-byte aligned");
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const moe_cache_config_t& cf = c->cfg;
+  const int E = cf.n_experts, K = cf.top_k, KS = c->KS, d = cf.d_model;
+
+  ProfSlot* ps = nullptr;
+  if (c->profiling) {
+    ps = &c->prof[c->prof_head];
+    int rc = drain_prof_slot(c, *ps);
+    if (rc != MOE_OK) return rc;
+    c->prof_head = (c->prof_head + 1) % kProfSlots;
+    HIPCHK(hipEventRecord(ps->e0, s));
+  }
+
+  const char* rw = static_cast<const char*>(c->w.router_w) + (size_t)layer * E * d * c->elem;
+  HIPCHK(launch_route(s, cf.dtype, x_dev, rw, logit_bias_dev, batch, E, K, KS, d, cf.norm_topk, c->t.idx, c->t.wpair,
+                      topk_idx_dev, topk_w_dev));
+
+  CacheCallArgs a{};
+  a.mode = 0; a.B = batch; a.K = K; a.KS = KS; a.E = E; a.C = c->C; a.P = c->P; a.n_shared = cf.n_shared;
+  a.policy = cf.policy; a.gamma = cf.gamma; a.trace_cap = cf.trace_capacity; a.seq = ++c->seq;
+  a.pin_ids = nullptr; a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
+  HIPCHK(launch_cache(s, c->layers[layer], c->t, a));
+  HIPCHK(hipEventRecord(c->ev_mail, s));
+  if (ps) HIPCHK(hipEventRecord(ps->e1, s));
+
+  FfnArgs fa{};
+  fa.x = x_dev;
+  fa.buffers = c->buffers + (size_t)layer * c->P * c->expert_bytes;
+  fa.shared = cf.n_shared ? static_cast<const char*>(c->w.shared_w) + (size_t)layer * cf.n_shared * c->expert_bytes
+                          : nullptr;
+  fa.expert_bytes = c->expert_bytes;
+  fa.P = c->P; fa.d = d; fa.f = cf.d_ff; fa.KS = KS;
+  fa.g_max = (int)std::min<size_t>((size_t)batch * K, (size_t)c->P) + cf.n_shared;
+  fa.max_count = batch;
+  fa.t = c->t; fa.h = c->h; fa.o = c->o;
+  const bool tiled = cf.pool_layout == MOE_LAYOUT_TILED;
+
+  // Experts that were already resident: their FFN starts right behind the cache
+  // kernel, before the host knows the miss list.
+  fa.pass = 0;
+  HIPCHK(tiled ? launch_ffn_tiled(s, fa, ps ? ps->e2 : nullptr) : launch_ffn_rowmajor(s, cf.dtype, fa, ps ? ps->e2 : nullptr));
+
+  HIPCHK(hipEventSynchronize(c->ev_mail));
+  const uint32_t got = __atomic_load_n(&c->mailbox->seq, __ATOMIC_ACQUIRE);
+  if (got != a.seq) return fail(MOE_ERR_TIMEOUT, "miss list of call %u not delivered (mailbox holds %u)", a.seq, got);
+  const Mailbox mb = *c->mailbox;
+  if (mb.status != MOE_OK)
+    return fail(mb.status, "call needs more spare expert buffers than staging_buffers=%d (batch %d)",
+                cf.staging_buffers, batch);
+  if (mb.n_miss > 0) {
+    int rc = issue_copies(c, layer, mb.n_miss);
+    if (rc != MOE_OK) return rc;
+    HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0));
+    c->copies_pending = false;
+    fa.pass = 1;
+    HIPCHK(tiled ? launch_ffn_tiled(s, fa, nullptr) : launch_ffn_rowmajor(s, cf.dtype, fa, nullptr));
+  }
+  if (ps) { HIPCHK(hipEventRecord(ps->e3, s)); ps->used = true; ps->mixed = mb.n_miss > 0; }
+  HIPCHK(launch_combine(s, cf.dtype, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, y_dev));
+
+  moe_cache_stats_t& st = c->stats[layer];
+  st.lookups += (uint64_t)batch * K;
+  st.hits += (uint64_t)mb.n_hits;
+  st.misses += (uint64_t)mb.n_miss;
+  st.evictions += (uint64_t)mb.n_evict;
+  st.bytes_h2d += (uint64_t)mb.n_miss * c->expert_bytes;
+  return MOE_OK;
+}
+
+int moe_cache_stats(const moe_cache_t* c, int32_t layer, moe_cache_stats_t* out) {
+  if (!c || !out) return fail(MOE_ERR_INVALID_ARG, "null argument");
+  if (layer < -1 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  moe_cache_stats_t s{};
+  const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? c->cfg.n_layers : layer + 1;
+  for (int l = l0; l < l1; ++l) {
+    const moe_cache_stats_t& v = c->stats[l];
+    s.lookups += v.lookups; s.hits += v.hits; s.misses += v.misses;
+    s.evictions += v.evictions; s.pin_loads += v.pin_loads; s.bytes_h2d += v.bytes_h2d;
+  }
+  *out = s;
+  return MOE_OK;
+}
+
+int moe_cache_read_trace(moe_cache_t* c, int32_t layer, moe_trace_rec_t* host_out, int64_t max_records,
+                         int64_t* n_out, int64_t* n_total) {
+  if (!c || !n_out) return fail(MOE_ERR_INVALID_ARG, "null argument");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  if (max_records < 0 || (max_records > 0 && !host_out)) return fail(MOE_ERR_INVALID_ARG, "bad output buffer");
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  HIPCHK(hipDeviceSynchronize());
+  int64_t total = 0;
+  HIPCHK(hipMemcpy(&total, c->layers[layer].scalars + SC_TRACE_N, 8, hipMemcpyDeviceToHost));
+  int64_t n = std::min<int64_t>(std::min<int64_t>(total, c->cfg.trace_capacity), max_records);
+  if (n > 0) HIPCHK(hipMemcpy(host_out, c->layers[layer].trace, (size_t)n * sizeof(moe_trace_rec_t), hipMemcpyDeviceToHost));
+  *n_out = n;
+  if (n_total) *n_total = total;
+  return MOE_OK;
+}
+
+int moe_cache_resident(moe_cache_t* c, int32_t layer, int32_t* host_out, int32_t* n_out) {
+  if (!c || !host_out || !n_out) return fail(MOE_ERR_INVALID_ARG, "null argument");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  HIPCHK(hipDeviceSynchronize());
+  std::vector<int32_t> ein(c->C);
+  HIPCHK(hipMemcpy(ein.data(), c->layers[layer].expert_in, (size_t)c->C * 4, hipMemcpyDeviceToHost));
+  std::vector<int32_t> res;
+  for (int v : ein) if (v >= 0) res.push_back(v);
+  std::sort(res.begin(), res.end());
+  for (size_t i = 0; i < res.size(); ++i) host_out[i] = res[i];
+  *n_out = (int32_t)res.size();
+  return MOE_OK;
+}
+
+int moe_cache_set_profiling(moe_cache_t* c, int32_t enabled) {
+  if (!c) return fail(MOE_ERR_INVALID_ARG, "null cache");
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  if (enabled && c->prof.empty()) {
+    c->prof.resize(kProfSlots);
+    c->cprof.resize(kProfSlots);
+    for (auto& p : c->prof) {
+      HIPCHK(hipEventCreate(&p.e0)); HIPCHK(hipEventCreate(&p.e1));
+      HIPCHK(hipEventCreate(&p.e2)); HIPCHK(hipEventCreate(&p.e3));
+    }
+    for (auto& p : c->cprof) { HIPCHK(hipEventCreate(&p.c0)); HIPCHK(hipEventCreate(&p.c1)); }
+  }
+  c->profiling = enabled != 0;
+  return MOE_OK;
+}
+
+int moe_cache_timing(moe_cache_t* c, moe_timing_t* out, int32_t clear) {
+  if (!c || !out) return fail(MOE_ERR_INVALID_ARG, "null argument");
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  for (auto& p : c->prof) {
+    int rc = drain_prof_slot(c, p);
+    if (rc != MOE_OK) return rc;
+  }
+  for (auto& cs : c->cprof) {
+    if (!cs.used) continue;
+    HIPCHK(hipEventSynchronize(cs.c1));
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, cs.c0, cs.c1));
+    c->timing.copy_ms += ms;
+    c->timing.copies += cs.n;
+    c->timing.copy_bytes += cs.bytes;
+    cs.used = false;
+  }
+  *out = c->timing;
+  if (clear) c->timing = moe_timing_t{};
+  return MOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,95 @@
+// Internal declarations shared by the host runtime and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe_cache.h"
+
+namespace moe {
+
+// Scalars of one layer's cache table (device, int64 each).
+enum { SC_CLOCK = 0, SC_NRES = 1, SC_NFREE = 2, SC_NZOMBIE = 3, SC_CALLSEQ = 4, SC_TRACE_N = 5, SC_COUNT = 8 };
+
+// Device-resident cache table of one layer.  A *slot* is a logical cache entry
+// (C of them); a *buffer* is a physical expert-sized block of HBM (P = C +
+// staging of them).  A slot owns exactly one buffer while it holds an expert.
+struct LayerState {
+  int32_t* expert_in;     // [C] expert held by the slot, -1 = empty (slots fill in index order)
+  uint64_t* tick;         // [C] value of the layer clock at the slot's last use
+  int32_t* buf_of_slot;   // [C]
+  int32_t* slot_of;       // [E] slot holding the expert, -1 = not resident
+  int32_t* free_buf;      // [P] stack of unused buffers
+  int32_t* zombie;        // [P] buffers released by the previous call, reusable from the next call on
+  uint32_t* used_stamp;   // [P] call sequence number of the buffer's last use
+  double* score;          // [E] discounted request count (gamma policy)
+  int64_t* scalars;       // [SC_COUNT]
+  moe_trace_rec_t* trace; // [trace_cap]
+};
+
+struct MissEntry { int32_t expert; int32_t buffer; };
+
+// Host-visible record the cache kernel fills for every call (pinned host memory).
+struct Mailbox {
+  uint32_t seq;        // written last: sequence number of the call this record belongs to
+  int32_t status;      // MOE_OK or MOE_ERR_STAGING_EXHAUSTED
+  int32_t n_miss;      // expert copies the host has to issue
+  int32_t n_evict;
+  int32_t n_groups;    // distinct expert buffers used by the call (incl. shared experts)
+  int32_t n_hits;
+  int32_t pad[2];
+};
+
+// Per-call scratch tables (device).
+struct CallTables {
+  int32_t* idx;          // [B][K]  selected experts, ascending id
+  float* wpair;          // [B][KS] gate weight per (token, expert) pair; 1 for shared experts
+  int32_t* pair_buf;     // [B*KS]  buffer id the pair reads (>= P: shared expert P + s)
+  int32_t* sorted_pair;  // [B*KS]  pairs ordered by buffer id, stable
+  int32_t* pos_of;       // [B*KS]  inverse of sorted_pair
+  int32_t* grp_buf;      // [G]
+  int32_t* grp_begin;    // [G]
+  int32_t* grp_count;    // [G]
+  int32_t* grp_miss;     // [G]     1 if the buffer is being filled by this call
+  int32_t* n_groups;     // [1]     number of groups of the call (0 if the call failed)
+};
+
+struct CacheCallArgs {
+  int32_t mode;          // 0 decode, 1 pin
+  int32_t B, K, KS, E, C, P, n_shared;
+  int32_t policy;
+  double gamma;
+  int32_t trace_cap;
+  uint32_t seq;
+  const int32_t* pin_ids; // mode 1: host-mapped list of K ids (B = 1)
+  Mailbox* mailbox;       // host-mapped
+  MissEntry* miss_list;   // host-mapped, [max_miss]
+  int32_t max_miss;
+};
+
+struct FfnArgs {
+  const void* x;           // [B][d]
+  const char* buffers;     // layer's expert buffers, P blocks
+  const char* shared;      // layer's shared expert blocks (may be null)
+  uint64_t expert_bytes;
+  int32_t P, d, f, KS;
+  int32_t g_max;           // grid rows launched; rows >= *t.n_groups exit at once
+  int32_t max_count;       // upper bound on tokens per group (= batch)
+  CallTables t;
+  void* h;                 // [B*KS][f]  fp32 (row-major path) or bf16 (tiled path)
+  float* o;                // [B*KS][d]
+  int32_t pass;            // 0: groups whose buffer was resident, 1: groups fetched by this call, 2: all
+};
+
+size_t cache_kernel_lds_bytes(const CacheCallArgs& a);
+
+hipError_t launch_route(hipStream_t s, int dtype, const void* x, const void* router_w, const float* bias,
+                        int B, int E, int K, int KS, int d, int norm_topk, int32_t* idx, float* wpair,
+                        int32_t* user_idx, float* user_w);
+hipError_t launch_cache(hipStream_t s, const LayerState& st, const CallTables& t, const CacheCallArgs& a);
+hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace);
+hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, hipEvent_t ev_mid);
+hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, hipEvent_t ev_mid);
+hipError_t launch_combine(hipStream_t s, int dtype, const float* o, const float* wpair, const int32_t* pos_of,
+                          int B, int KS, int d, void* y);
+
+}  // namespace moe

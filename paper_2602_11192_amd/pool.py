@@ -1,0 +1,93 @@
+"""Places a synthetic workload's parameters where the library expects them:
+router weights and shared experts in HBM, routed experts in a pinned host pool
+(optionally permuted into the tiled layout).  Data movement only."""
+from __future__ import annotations
+
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(cfg):
+    return torch.float32 if cfg.dtype == "fp32" else torch.bfloat16
+
+
+def moe_dtype(cfg):
+    return B.MOE_DTYPE_FP32 if cfg.dtype == "fp32" else B.MOE_DTYPE_BF16
+
+
+def to_device(arr: np.ndarray, device="cuda:0") -> torch.Tensor:
+    """Stored numpy array (float32, or uint16 bf16 bit patterns) -> device tensor of the same values."""
+    if arr.dtype == np.uint16:
+        return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr)).to(device)
+
+
+def to_numpy(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> float32 numpy (bf16 widened exactly)."""
+    return t.detach().float().cpu().numpy()
+
+
+def _block(mats, cfg, tiled: bool) -> np.ndarray:
+    flat = np.concatenate([m.reshape(-1) for m in mats])
+    if not tiled:
+        return flat
+    out = np.empty_like(flat)
+    B.moe_pack_expert(flat, out, cfg.d_model, cfg.d_ff)
+    return out
+
+
+def build_pool(wl, tiled: bool, workers: int = 8) -> torch.Tensor:
+    """Pinned host tensor [L][E] expert blocks (flat), storage dtype."""
+    cfg = wl.cfg
+    per = 3 * cfg.d_model * cfg.d_ff
+    n = cfg.n_layers * cfg.n_experts
+    tdt = torch.float32 if cfg.dtype == "fp32" else torch.int16
+    pool = torch.empty(n * per, dtype=tdt, pin_memory=torch.cuda.is_available())
+    view = pool.numpy()
+    if cfg.dtype != "fp32":
+        view = view.view(np.uint16)
+
+    def fill(i):
+        l, e = divmod(i, cfg.n_experts)
+        view[i * per:(i + 1) * per] = _block(wl.expert(l, e), cfg, tiled)
+
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        list(ex.map(fill, range(n)))
+    return pool
+
+
+def build_router(wl, device="cuda:0") -> torch.Tensor:
+    cfg = wl.cfg
+    return to_device(np.stack([wl.router_w(l) for l in range(cfg.n_layers)]), device)
+
+
+def build_shared(wl, tiled: bool, device="cuda:0"):
+    cfg = wl.cfg
+    if cfg.n_shared == 0:
+        return None
+    blocks = [_block(wl.shared(l, s), cfg, tiled) for l in range(cfg.n_layers) for s in range(cfg.n_shared)]
+    return to_device(np.concatenate(blocks), device)
+
+
+def make_cache(wl, *, tiled=None, capacity=None, max_batch=1, staging_buffers=0, trace_capacity=0,
+               policy=B.MOE_POLICY_LRU, gamma=1.0, norm_topk=None, device="cuda:0", pool=None):
+    """Build pool + router (+ shared) for `wl` and create the native cache."""
+    cfg = wl.cfg
+    if tiled is None:
+        tiled = cfg.dtype == "bf16"
+    pool = build_pool(wl, tiled) if pool is None else pool
+    router = build_router(wl, device)
+    shared = build_shared(wl, tiled, device)
+    cache = B.MoECache(
+        n_layers=cfg.n_layers, n_experts=cfg.n_experts, n_shared=cfg.n_shared, top_k=cfg.top_k,
+        d_model=cfg.d_model, d_ff=cfg.d_ff, capacity=cfg.capacity if capacity is None else capacity,
+        dtype=moe_dtype(cfg), norm_topk=cfg.norm_topk if norm_topk is None else norm_topk, policy=policy,
+        gamma=gamma, max_batch=max_batch, staging_buffers=staging_buffers,
+        device_id=torch.device(device).index or 0, trace_capacity=trace_capacity,
+        pool_layout=B.MOE_LAYOUT_TILED if tiled else B.MOE_LAYOUT_ROWMAJOR,
+        router_w=router, expert_pool=pool, shared_w=shared)
+    return cache

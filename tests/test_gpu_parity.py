@@ -1,0 +1,156 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
+same seeded inputs.  Routing indices, cache traces, statistics and resident sets
+must match exactly; outputs within the stated tolerance (fp32 1e-4, bf16 2e-2 of
+the token's largest output magnitude)."""
+import numpy as np
+import pytest
+
+import oracle
+from tests.helpers import TOL, OracleStack, compare_traces_and_stats, rel_err, run_sequence_serial
+from workload import MoEConfig, Workload, get_config, widen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    return t
+
+
+@pytest.fixture(scope="module")
+def P():
+    from paper_2602_11192_amd import pool
+    return pool
+
+
+def small_cfg(**kw):
+    base = dict(name="small_bf16", cfg_id=11, dtype="bf16", n_layers=2, d_model=128, d_ff=96, n_experts=16,
+                n_shared=0, top_k=4, capacity=6, n_seqs=3, n_steps=24, prefill_len=0, beta=2.0, pref_lo=4,
+                pref_hi=4, delta=1e-3)
+    base.update(kw)
+    return MoEConfig(**base)
+
+
+# ------------------------------------------------------------------ config 1
+@pytest.mark.parametrize("pins", [True, False])
+def test_tiny_fp32_full_workload(torch, P, pins):
+    cfg = get_config("tiny_fp32")
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, trace_capacity=4096)
+    ost = OracleStack(wl)
+    worst, n_y, traces = run_sequence_serial(wl, cache, ost, pins=pins, torch=torch)
+    assert n_y == cfg.n_seqs * cfg.n_steps and worst <= TOL["fp32"]
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    st = cache.moe_cache_stats()
+    assert st["hits"] + st["misses"] == st["lookups"] == cfg.n_seqs * cfg.n_steps * cfg.top_k
+    cache.close()
+
+
+# ------------------------------------------------- small bf16, both layouts
+@pytest.mark.parametrize("tiled", [False, True])
+@pytest.mark.parametrize("norm_topk", [1, 0])
+def test_small_bf16_sequence_serial(torch, P, tiled, norm_topk):
+    cfg = small_cfg(norm_topk=norm_topk)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=tiled, trace_capacity=4096)
+    ost = OracleStack(wl)
+    worst, n_y, traces = run_sequence_serial(wl, cache, ost, torch=torch)
+    assert n_y == cfg.n_seqs * cfg.n_steps * cfg.n_layers
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+@pytest.mark.parametrize("tiled", [False, True])
+def test_small_bf16_shared_experts(torch, P, tiled):
+    cfg = small_cfg(n_shared=2, d_ff=160, d_model=96)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=tiled, trace_capacity=4096)
+    ost = OracleStack(wl)
+    _, _, traces = run_sequence_serial(wl, cache, ost, torch=torch, seqs=[0, 1], steps=12)
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+def batched_step(torch, P, wl, cache, ost, layer, rows, step):
+    """One call with one token from each sequence in `rows`."""
+    cfg = wl.cfg
+    xs = np.stack([wl.tokens(s)[step] for s in rows])
+    bias = np.stack([wl.bias(layer, s) for s in rows])
+    x_dev = P.to_device(xs)
+    y = torch.empty((len(rows), cfg.d_model), dtype=P.torch_dtype(cfg), device="cuda:0")
+    idx = torch.empty((len(rows), cfg.top_k), dtype=torch.int32, device="cuda:0")
+    cache.moe_layer_decode(layer, x_dev, y, torch.from_numpy(bias).cuda(), idx, None)
+    res = ost.decode(layer, widen(xs), bias)
+    torch.cuda.synchronize()
+    assert idx.cpu().numpy().tolist() == res.idx.tolist()
+    err = rel_err(P.to_numpy(y), res.y)
+    assert err.max() <= TOL[cfg.dtype], err
+    return res.trace
+
+
+@pytest.mark.parametrize("tiled", [False, True])
+@pytest.mark.parametrize("batch", [3, 7])
+def test_small_bf16_batched_with_evictions_inside_a_call(torch, P, tiled, batch):
+    # batch * K > C: a call evicts experts that earlier tokens of the same call hit,
+    # which exercises the spare-buffer indirection.
+    cfg = small_cfg(n_seqs=7, n_steps=10, n_layers=1, capacity=5)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=tiled, max_batch=batch, staging_buffers=batch * cfg.top_k, trace_capacity=8192)
+    ost = OracleStack(wl)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, list(range(batch)), step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+def test_staging_exhausted_leaves_cache_unchanged(torch, P):
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(n_seqs=8, n_steps=4, n_layers=1, capacity=4, pref_lo=0, pref_hi=0, beta=0.0)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=8, staging_buffers=0, trace_capacity=512)
+    ost = OracleStack(wl)
+    trace = batched_step(torch, P, wl, cache, ost, 0, [0], 0)          # a call that fits
+    before = (cache.moe_cache_resident(0), cache.moe_cache_stats(0), cache.moe_cache_read_trace(0)[1])
+    xs = np.stack([wl.tokens(s)[1] for s in range(8)])
+    y = torch.empty((8, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(B.MoeError) as ei:
+        cache.moe_layer_decode(0, P.to_device(xs), y)
+    assert ei.value.code == B.MOE_ERR_STAGING_EXHAUSTED
+    torch.cuda.synchronize()
+    assert (cache.moe_cache_resident(0), cache.moe_cache_stats(0), cache.moe_cache_read_trace(0)[1]) == before
+    trace += batched_step(torch, P, wl, cache, ost, 0, [1], 1)          # and the cache still works
+    compare_traces_and_stats(cache, ost, [trace], cfg.expert_bytes)
+    cache.close()
+
+
+@pytest.mark.parametrize("gamma", [1.0, 0.9])
+def test_small_bf16_gamma_policy(torch, P, gamma):
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(n_layers=1, n_steps=40)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, trace_capacity=4096, policy=B.MOE_POLICY_GAMMA, gamma=gamma)
+    ost = OracleStack(wl, policy=oracle.POLICY_GAMMA, gamma=gamma)
+    _, _, traces = run_sequence_serial(wl, cache, ost, torch=torch, y_every=8)
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+def test_error_paths_on_device(torch, P):
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(n_layers=1)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=2)
+    x = torch.zeros((3, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    y = torch.zeros_like(x)
+    for call in (lambda: cache.moe_layer_decode(0, x, y),                       # batch > max_batch
+                 lambda: cache.moe_layer_decode(1, x[:1], y[:1]),               # layer out of range
+                 lambda: cache.moe_cache_prefill_pins(0, [1, 1]),               # duplicate ids
+                 lambda: cache.moe_cache_prefill_pins(0, [cfg.n_experts]),      # id out of range
+                 lambda: cache.moe_cache_prefill_pins(0, list(range(cfg.capacity + 1)))):
+        with pytest.raises(B.MoeError) as ei:
+            call()
+        assert ei.value.code == B.MOE_ERR_INVALID_ARG
+    cache.close()

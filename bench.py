@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE decode hot path on one MI355X.
+
+A step is one pass of the whole hot path over the OLMoE-like workload: 16
+sequences, served one after the other at batch 1 (the paper's main setting);
+per sequence the layer's cache is emptied, the prefetch set is preloaded, then
+128 tokens are decoded through router -> gating -> cache lookup (+ host->device
+fetch of missed experts) -> SwiGLU experts -> combine.  All inputs (hidden
+states, biases, router, pinned expert pool) are resident before the timed
+region.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published
+PCIE_PEAK_GBPS = 64.0       # PCIe 5 x16, one direction, nominal
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="olmoe_like")
+    ap.add_argument("--cpu-baseline-tokens", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+class Runner:
+    """Pre-marshalled arguments for the per-token calls (keeps the Python loop thin)."""
+
+    def __init__(self, wl, cache, torch, P):
+        cfg = wl.cfg
+        self.cfg, self.cache, self.torch = cfg, cache, torch
+        self.lib = P.B.lib
+        self.h = cache._h
+        self.x = [P.to_device(wl.tokens(s)) for s in range(cfg.n_seqs)]
+        self.bias = [[torch.from_numpy(wl.bias(l, s)[None, :].copy()).cuda() for s in range(cfg.n_seqs)]
+                     for l in range(cfg.n_layers)]
+        self.y = torch.empty((cfg.n_seqs, cfg.d_model), dtype=P.torch_dtype(cfg), device="cuda:0")
+        self.pins = [[wl.prefetch_list(l, s) for s in range(cfg.n_seqs)] for l in range(cfg.n_layers)]
+        row = cfg.d_model * cfg.elem_bytes
+        self.xp = [[C.c_void_p(x.data_ptr() + t * row) for t in range(cfg.n_steps)] for x in self.x]
+        self.bp = [[C.c_void_p(b.data_ptr()) for b in bl] for bl in self.bias]
+        self.yp = C.c_void_p(self.y.data_ptr())
+        self.sp = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def _chk(self, rc):
+        if rc != 0:
+            raise RuntimeError("moe_layer_decode failed: %d %s" % (rc, self.lib.moe_last_error().decode()))
+
+    def pass_sequence_serial(self, pins=True):
+        """One step: every sequence, batch 1, reset + prefetch per sequence.  Returns tokens decoded."""
+        cfg, dec, h, yp, sp = self.cfg, self.lib.moe_layer_decode, self.h, self.yp, self.sp
+        for s in range(cfg.n_seqs):
+            self.cache.moe_cache_reset(-1)
+            if pins:
+                for l in range(cfg.n_layers):
+                    self.cache.moe_cache_prefill_pins(l, self.pins[l][s])
+            xp = self.xp[s]
+            for t in range(cfg.n_steps):
+                for l in range(cfg.n_layers):
+                    rc = dec(h, l, xp[t], self.bp[l][s], 1, yp, None, None, sp)
+                    if rc:
+                        self._chk(rc)
+        return cfg.n_seqs * cfg.n_steps
+
+    def pass_resident(self):
+        """Same tokens, no resets: for a cache that holds every expert."""
+        cfg, dec, h, yp, sp = self.cfg, self.lib.moe_layer_decode, self.h, self.yp, self.sp
+        for s in range(cfg.n_seqs):
+            xp = self.xp[s]
+            for t in range(cfg.n_steps):
+                for l in range(cfg.n_layers):
+                    rc = dec(h, l, xp[t], self.bp[l][s], 1, yp, None, None, sp)
+                    if rc:
+                        self._chk(rc)
+        return cfg.n_seqs * cfg.n_steps
+
+
+def timed(torch, fn, steps):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n = 0
+    for _ in range(steps):
+        n += fn()
+    torch.cuda.synchronize()
+    return n, time.perf_counter() - t0
+
+
+def cpu_baseline(wl, n_tokens):
+    """The oracle as it stands, all host cores through its OpenMP row loops, on the first tokens of the workload."""
+    import numpy as np
+    import oracle
+    from tests.helpers import OracleStack
+    from workload import widen
+    cfg = wl.cfg
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    cores = max(1, min(cores, 16))
+    oracle.set_threads(cores)
+    ost = OracleStack(wl, keep=cfg.n_experts * cfg.n_layers)
+    for l in range(cfg.n_layers):                      # parameter conversion is not part of the timed work
+        for e in range(cfg.n_experts):
+            ost.expert(l, e)
+    done, t_used = 0, 0.0
+    for s in range(cfg.n_seqs):
+        x32 = widen(wl.tokens(s))
+        for c in ost.caches:
+            c.reset()
+        for l in range(cfg.n_layers):
+            ost.caches[l].pin(wl.prefetch_list(l, s))
+        biases = [wl.bias(l, s)[None, :] for l in range(cfg.n_layers)]
+        t0 = time.perf_counter()
+        for t in range(cfg.n_steps):
+            for l in range(cfg.n_layers):
+                ost.decode(l, x32[t:t + 1], biases[l])
+            done += 1
+            if done >= n_tokens:
+                break
+        t_used += time.perf_counter() - t0
+        if done >= n_tokens:
+            break
+    oracle.set_threads(1)
+    return {"value": done / t_used, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "first %d decode tokens of the workload (sequence-serial, batch 1, all %d layer(s)), "
+                      "fp64 oracle with OpenMP over output rows" % (done, cfg.n_layers)}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build is single-GPU (the hot path has no cross-GPU step); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2602_11192_amd import pool as P
+    from workload import Workload, get_config
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+
+    cfg = get_config(a.workload)
+    wl = Workload(cfg)
+    t0 = time.perf_counter()
+    pool = P.build_pool(wl, tiled=True)
+    for s in range(cfg.n_seqs):
+        wl.tokens(s)
+    t_gen = time.perf_counter() - t0
+
+    K, d, f, eb = cfg.top_k, cfg.d_model, cfg.d_ff, cfg.expert_bytes
+    s_el = cfg.elem_bytes
+
+    # ---------------- the workload as stated: capacity C, prefetch per sequence ----------------
+    cache = P.make_cache(wl, tiled=True, pool=pool)
+    run = Runner(wl, cache, torch, P)
+    for _ in range(a.warmup):
+        run.pass_sequence_serial()
+    cache.moe_cache_reset(-1, clear_stats=True)
+    n_tok, dt = timed(torch, run.pass_sequence_serial, a.steps)
+    st = cache.moe_cache_stats()
+    value = n_tok / dt
+
+    # same steps again with HIP-event timing of the kernels and copies (events sit on the launch stream)
+    cache.moe_cache_set_profiling(True)
+    cache.moe_cache_timing(clear=True)
+    n_tok_p, dt_p = timed(torch, run.pass_sequence_serial, a.steps)
+    tm = cache.moe_cache_timing(clear=True)
+    cache.moe_cache_set_profiling(False)
+    cache.close()
+
+    # ---------------- resident path: every expert on the device ----------------
+    rcache = P.make_cache(wl, tiled=True, pool=pool, capacity=cfg.n_experts)
+    rrun = Runner(wl, rcache, torch, P)
+    for l in range(cfg.n_layers):
+        rcache.moe_cache_prefill_pins(l, list(range(cfg.n_experts)))
+    for _ in range(max(1, a.warmup)):
+        rrun.pass_resident()
+    n_tok_r, dt_r = timed(torch, rrun.pass_resident, a.steps)
+    rcache.moe_cache_set_profiling(True)
+    rcache.moe_cache_timing(clear=True)
+    timed(torch, rrun.pass_resident, a.steps)
+    rtm = rcache.moe_cache_timing(clear=True)
+    rcache.close()
+
+    # ---------------- roofline of the dominant kernel (gate/up projection of the K experts) ----------------
+    # algorithmic bytes of one launch at batch 1: gate and up matrices of K experts, the token, the K hidden rows
+    gu_bytes = K * 2 * d * f * s_el + d * s_el + K * f * s_el
+    gu_ms = tm["ffn_gate_up_ms"] / max(1, tm["ffn_launches"])
+    achieved = gu_bytes / (gu_ms * 1e-3) / 1e9 if gu_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("gate_up_bytes_per_launch")
+    roofline = {"bound": "hbm", "kernel": "ffn_tiled_kernel<2,...> (gate/up + SiLU*mul of the K selected experts)",
+                "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                "traffic": traffic, "bytes_per_launch": gu_bytes, "avg_launch_ms": gu_ms,
+                "launches_timed": tm["ffn_launches"],
+                "source": "HIP events on the launch stream, same steps re-run with event timing on; "
+                          "launches of calls without a miss"}
+
+    layer_bytes = K * eb + cfg.n_experts * d * s_el + 2 * d * s_el + cfg.n_experts * 4
+    res_tok_s = n_tok_r / dt_r
+    ffn_ms_r = (rtm["ffn_gate_up_ms"] + rtm["ffn_down_ms"]) / max(1, rtm["ffn_launches"])
+    out = {
+        "metric": "decode tokens/sec per MoE layer stack at 1 MI355X",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt / a.steps * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d layer(s), d=%d, d_ff=%d, E=%d, top-%d, capacity %d, %d sequences x %d decode "
+                               "steps, sequence-serial batch 1 with per-sequence prefetch, LRU" %
+                               (cfg.name, cfg.n_layers, d, f, cfg.n_experts, K, cfg.capacity, cfg.n_seqs, cfg.n_steps),
+                   "tokens_per_step": cfg.n_seqs * cfg.n_steps},
+        "cache_hit_rate": st["hits"] / max(1, st["lookups"]),
+        "misses_per_token": st["misses"] / max(1, n_tok),
+        "roofline": roofline,
+        "pcie": {"achieved": tm["copy_bytes"] / (tm["copy_ms"] * 1e-3) / 1e9 if tm["copy_ms"] > 0 else None,
+                 "peak": PCIE_PEAK_GBPS, "unit": "GB/s", "copies": tm["copies"], "copy_ms_total": tm["copy_ms"]},
+        "resident_path": {"tokens_per_s": res_tok_s, "us_per_token": 1e6 / res_tok_s,
+                          "algorithmic_GBps_whole_call": layer_bytes * cfg.n_layers * res_tok_s / 1e9,
+                          "frac_of_hbm_peak_whole_call": layer_bytes * cfg.n_layers * res_tok_s / 1e9 / HBM_PEAK_GBPS,
+                          "ffn_kernels_us": ffn_ms_r * 1e3,
+                          "gate_up_us": rtm["ffn_gate_up_ms"] / max(1, rtm["ffn_launches"]) * 1e3,
+                          "down_us": rtm["ffn_down_ms"] / max(1, rtm["ffn_launches"]) * 1e3,
+                          "route_cache_us": rtm["route_ms"] / max(1, rtm["ffn_launches"]) * 1e3},
+        "profiled_rerun_tokens_per_s": n_tok_p / dt_p,
+        "setup_s": t_gen,
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, a.cpu_baseline_tokens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

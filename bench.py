@@ -204,7 +204,8 @@ def main():
                 "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                 "traffic": traffic, "bytes_per_launch": gu_bytes, "avg_launch_ms": gu_ms,
                 "launches_timed": tm["ffn_launches"],
-                "source": "HIP events on the launch stream, same steps re-run with event timing on; "
+                "source": "HIP events attached to the kernel's dispatch on the launch stream "
+                          "(hipExtLaunchKernelGGL start/stop), same steps re-run with event timing on; "
                           "launches of calls without a miss"}
 
     layer_bytes = K * eb + cfg.n_experts * d * s_el + 2 * d * s_el + cfg.n_experts * 4

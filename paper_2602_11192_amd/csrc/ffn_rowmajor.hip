@@ -85,19 +85,17 @@ combine_kernel(const float* __restrict__ o, const float* __restrict__ wpair, con
 
 }  // namespace
 
-hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, hipEvent_t ev_mid) {
+hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, KernelEvents e1, KernelEvents e2) {
   if (a.g_max <= 0) return hipSuccess;
   dim3 block(64 * kRowsPerBlock);
   dim3 g1((a.f + kRowsPerBlock - 1) / kRowsPerBlock, a.g_max);
   dim3 g2((a.d + kRowsPerBlock - 1) / kRowsPerBlock, a.g_max);
   if (dtype == MOE_DTYPE_FP32) {
-    hipLaunchKernelGGL(gate_up_rowmajor<float>, g1, block, 0, s, a);
-    if (ev_mid) (void)hipEventRecord(ev_mid, s);
-    hipLaunchKernelGGL(down_rowmajor<float>, g2, block, 0, s, a);
+    launch_timed(gate_up_rowmajor<float>, g1, block, 0, s, e1, a);
+    launch_timed(down_rowmajor<float>, g2, block, 0, s, e2, a);
   } else {
-    hipLaunchKernelGGL(gate_up_rowmajor<uint16_t>, g1, block, 0, s, a);
-    if (ev_mid) (void)hipEventRecord(ev_mid, s);
-    hipLaunchKernelGGL(down_rowmajor<uint16_t>, g2, block, 0, s, a);
+    launch_timed(gate_up_rowmajor<uint16_t>, g1, block, 0, s, e1, a);
+    launch_timed(down_rowmajor<uint16_t>, g2, block, 0, s, e2, a);
   }
   return hipGetLastError();
 }

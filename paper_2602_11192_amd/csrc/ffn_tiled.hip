@@ -142,19 +142,17 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_tiled_kernel(FfnArgs a) {
 
 }  // namespace
 
-hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, hipEvent_t ev_mid) {
+hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, KernelEvents e1, KernelEvents e2) {
   if (a.g_max <= 0) return hipSuccess;
   constexpr int WAVES = 8, CH = 8;
   dim3 block(64 * WAVES);
   dim3 g1(a.f / 16, a.g_max), g2(a.d / 16, a.g_max);
   if (a.max_count <= 16) {
-    hipLaunchKernelGGL((ffn_tiled_kernel<2, WAVES, CH, 1>), g1, block, 0, s, a);
-    if (ev_mid) (void)hipEventRecord(ev_mid, s);
-    hipLaunchKernelGGL((ffn_tiled_kernel<1, WAVES, CH, 1>), g2, block, 0, s, a);
+    launch_timed(ffn_tiled_kernel<2, WAVES, CH, 1>, g1, block, 0, s, e1, a);
+    launch_timed(ffn_tiled_kernel<1, WAVES, CH, 1>, g2, block, 0, s, e2, a);
   } else {
-    hipLaunchKernelGGL((ffn_tiled_kernel<2, WAVES, CH, 2>), g1, block, 0, s, a);
-    if (ev_mid) (void)hipEventRecord(ev_mid, s);
-    hipLaunchKernelGGL((ffn_tiled_kernel<1, WAVES, CH, 2>), g2, block, 0, s, a);
+    launch_timed(ffn_tiled_kernel<2, WAVES, CH, 2>, g1, block, 0, s, e1, a);
+    launch_timed(ffn_tiled_kernel<1, WAVES, CH, 2>, g2, block, 0, s, e2, a);
   }
   return hipGetLastError();
 }

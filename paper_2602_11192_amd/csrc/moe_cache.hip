@@ -45,9 +45,9 @@ int fail(int code, const char* fmt, ...) {
 constexpr int kProfSlots = 512;
 
 struct ProfSlot {
-  hipEvent_t e0 = nullptr, e1 = nullptr, e2 = nullptr, e3 = nullptr;  // route start, ffn start, ffn mid, ffn end
+  KernelEvents route, gate_up, down;   // attached to the dispatches of the three main kernels of a call
   bool used = false;
-  bool mixed = false;  // the call also fetched experts: its FFN span includes copy waits, not added to the sums
+  bool mixed = false;  // the call also fetched experts: its resident-pass FFN covers only part of the K experts
 };
 struct CopySlot {
   hipEvent_t c0 = nullptr, c1 = nullptr;
@@ -73,6 +73,7 @@ struct moe_cache {
   char* call_mem = nullptr;
   void* h = nullptr;
   float* o = nullptr;
+  int32_t* arrive = nullptr;
 
   char* host_mem = nullptr;       // pinned: mailbox | pin ids | miss list
   Mailbox* mailbox = nullptr;
@@ -157,12 +158,11 @@ int validate(const moe_cache_config_t* c, const moe_weights_t* w) {
 
 void free_all(moe_cache* c) {
   if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
-  for (auto& p : c->prof) {
-    if (p.e0) (void)hipEventDestroy(p.e0);
-    if (p.e1) (void)hipEventDestroy(p.e1);
-    if (p.e2) (void)hipEventDestroy(p.e2);
-    if (p.e3) (void)hipEventDestroy(p.e3);
-  }
+  for (auto& p : c->prof)
+    for (KernelEvents* ke : {&p.route, &p.gate_up, &p.down}) {
+      if (ke->start) (void)hipEventDestroy(ke->start);
+      if (ke->stop) (void)hipEventDestroy(ke->stop);
+    }
   for (auto& p : c->cprof) {
     if (p.c0) (void)hipEventDestroy(p.c0);
     if (p.c1) (void)hipEventDestroy(p.c1);
@@ -229,11 +229,11 @@ int issue_copies(moe_cache* c, int layer, int n) {
 
 int drain_prof_slot(moe_cache* c, ProfSlot& p) {
   if (!p.used) return MOE_OK;
-  HIPCHK(hipEventSynchronize(p.e3));
+  HIPCHK(hipEventSynchronize(p.down.stop));
   float a = 0.f, b = 0.f, r = 0.f;
-  HIPCHK(hipEventElapsedTime(&r, p.e0, p.e1));
-  HIPCHK(hipEventElapsedTime(&a, p.e1, p.e2));
-  HIPCHK(hipEventElapsedTime(&b, p.e2, p.e3));
+  HIPCHK(hipEventElapsedTime(&r, p.route.start, p.route.stop));
+  HIPCHK(hipEventElapsedTime(&a, p.gate_up.start, p.gate_up.stop));
+  HIPCHK(hipEventElapsedTime(&b, p.down.start, p.down.stop));
   c->timing.route_ms += r;
   if (!p.mixed) {
     c->timing.ffn_gate_up_ms += a;
@@ -321,9 +321,8 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->max_miss = (int)std::max<size_t>((size_t)Bm * K, (size_t)C);
   c->stats.assign(L, moe_cache_stats_t{});
 
-  CacheCallArgs probe{};
-  probe.E = E; probe.C = C; probe.P = P; probe.n_shared = cfg->n_shared;
-  if (cache_kernel_lds_bytes(probe) > 60 * 1024) {
+  if (route_cache_lds_bytes(E, C, P, cfg->n_shared, (int)std::min<size_t>(Bm, kStageMaxPairs / KS), K, KS) > 64 * 1024 ||
+      route_cache_lds_bytes(E, C, P, cfg->n_shared, 1, C, C) > 64 * 1024) {
     delete c;
     return fail(MOE_ERR_UNSUPPORTED, "cache table of this size does not fit in LDS");
   }
@@ -348,7 +347,6 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   const size_t o_scal = per_layer; per_layer += align_up((size_t)SC_COUNT * 8, 16);
   const size_t o_ein = per_layer; per_layer += align_up((size_t)C * 4, 16);
   const size_t o_bos = per_layer; per_layer += align_up((size_t)C * 4, 16);
-  const size_t o_sof = per_layer; per_layer += align_up((size_t)E * 4, 16);
   const size_t o_free = per_layer; per_layer += align_up((size_t)P * 4, 16);
   const size_t o_zom = per_layer; per_layer += align_up((size_t)P * 4, 16);
   const size_t o_used = per_layer; per_layer += align_up((size_t)P * 4, 16);
@@ -364,7 +362,6 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
     s.scalars = reinterpret_cast<int64_t*>(b + o_scal);
     s.expert_in = reinterpret_cast<int32_t*>(b + o_ein);
     s.buf_of_slot = reinterpret_cast<int32_t*>(b + o_bos);
-    s.slot_of = reinterpret_cast<int32_t*>(b + o_sof);
     s.free_buf = reinterpret_cast<int32_t*>(b + o_free);
     s.zombie = reinterpret_cast<int32_t*>(b + o_zom);
     s.used_stamp = reinterpret_cast<uint32_t*>(b + o_used);
@@ -383,6 +380,7 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   const size_t o_gc = cm; cm += align_up((size_t)c->G * 4, 16);
   const size_t o_gm = cm; cm += align_up((size_t)c->G * 4, 16);
   const size_t o_ng = cm; cm += 16;
+  const size_t o_arr = cm; cm += 16;
   CREATE_CHK(hipMalloc(&c->call_mem, cm), MOE_ERR_HIP);
   CREATE_CHK(hipMemset(c->call_mem, 0, cm), MOE_ERR_HIP);
   c->t.idx = reinterpret_cast<int32_t*>(c->call_mem + o_idx);
@@ -395,6 +393,7 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->t.grp_count = reinterpret_cast<int32_t*>(c->call_mem + o_gc);
   c->t.grp_miss = reinterpret_cast<int32_t*>(c->call_mem + o_gm);
   c->t.n_groups = reinterpret_cast<int32_t*>(c->call_mem + o_ng);
+  c->arrive = reinterpret_cast<int32_t*>(c->call_mem + o_arr);
   CREATE_CHK(hipMalloc(&c->h, NP * cfg->d_ff * 4), MOE_ERR_HIP);
   CREATE_CHK(hipMalloc(reinterpret_cast<void**>(&c->o), NP * cfg->d_model * 4), MOE_ERR_HIP);
 
@@ -465,7 +464,7 @@ int moe_cache_prefill_pins(moe_cache_t* c, int32_t layer, const int32_t* expert_
   a.trace_cap = c->cfg.trace_capacity; a.seq = ++c->seq; a.pin_ids = c->pin_ids;
   a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
   if (c->copies_pending) { HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0)); c->copies_pending = false; }
-  HIPCHK(launch_cache(s, c->layers[layer], c->t, a));
+  HIPCHK(launch_pin(s, c->layers[layer], c->t, a));
   int rc = wait_mailbox(c, s, a.seq);
   if (rc != MOE_OK) return rc;
   const Mailbox mb = *c->mailbox;
@@ -503,20 +502,22 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
     int rc = drain_prof_slot(c, *ps);
     if (rc != MOE_OK) return rc;
     c->prof_head = (c->prof_head + 1) % kProfSlots;
-    HIPCHK(hipEventRecord(ps->e0, s));
   }
 
-  const char* rw = static_cast<const char*>(c->w.router_w) + (size_t)layer * E * d * c->elem;
-  HIPCHK(launch_route(s, cf.dtype, x_dev, rw, logit_bias_dev, batch, E, K, KS, d, cf.norm_topk, c->t.idx, c->t.wpair,
-                      topk_idx_dev, topk_w_dev));
+  RouteArgs ra{};
+  ra.x = x_dev;
+  ra.router_w = static_cast<const char*>(c->w.router_w) + (size_t)layer * E * d * c->elem;
+  ra.bias = logit_bias_dev;
+  ra.d = d; ra.norm_topk = cf.norm_topk;
+  ra.user_idx = topk_idx_dev; ra.user_w = topk_w_dev;
+  ra.arrive = c->arrive;
 
   CacheCallArgs a{};
   a.mode = 0; a.B = batch; a.K = K; a.KS = KS; a.E = E; a.C = c->C; a.P = c->P; a.n_shared = cf.n_shared;
   a.policy = cf.policy; a.gamma = cf.gamma; a.trace_cap = cf.trace_capacity; a.seq = ++c->seq;
   a.pin_ids = nullptr; a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
-  HIPCHK(launch_cache(s, c->layers[layer], c->t, a));
+  HIPCHK(launch_route_cache(s, cf.dtype, ra, c->layers[layer], c->t, a, ps ? ps->route : KernelEvents{}));
   HIPCHK(hipEventRecord(c->ev_mail, s));
-  if (ps) HIPCHK(hipEventRecord(ps->e1, s));
 
   FfnArgs fa{};
   fa.x = x_dev;
@@ -529,11 +530,12 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   fa.max_count = batch;
   fa.t = c->t; fa.h = c->h; fa.o = c->o;
   const bool tiled = cf.pool_layout == MOE_LAYOUT_TILED;
+  const KernelEvents ke1 = ps ? ps->gate_up : KernelEvents{}, ke2 = ps ? ps->down : KernelEvents{};
 
   // Experts that were already resident: their FFN starts right behind the cache
-  // kernel, before the host knows the miss list.
+  // lookups, before the host knows the miss list.
   fa.pass = 0;
-  HIPCHK(tiled ? launch_ffn_tiled(s, fa, ps ? ps->e2 : nullptr) : launch_ffn_rowmajor(s, cf.dtype, fa, ps ? ps->e2 : nullptr));
+  HIPCHK(tiled ? launch_ffn_tiled(s, fa, ke1, ke2) : launch_ffn_rowmajor(s, cf.dtype, fa, ke1, ke2));
 
   HIPCHK(hipEventSynchronize(c->ev_mail));
   const uint32_t got = __atomic_load_n(&c->mailbox->seq, __ATOMIC_ACQUIRE);
@@ -548,9 +550,10 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
     HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0));
     c->copies_pending = false;
     fa.pass = 1;
-    HIPCHK(tiled ? launch_ffn_tiled(s, fa, nullptr) : launch_ffn_rowmajor(s, cf.dtype, fa, nullptr));
+    HIPCHK(tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
+                 : launch_ffn_rowmajor(s, cf.dtype, fa, KernelEvents{}, KernelEvents{}));
   }
-  if (ps) { HIPCHK(hipEventRecord(ps->e3, s)); ps->used = true; ps->mixed = mb.n_miss > 0; }
+  if (ps) { ps->used = true; ps->mixed = mb.n_miss > 0; }
   HIPCHK(launch_combine(s, cf.dtype, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, y_dev));
 
   moe_cache_stats_t& st = c->stats[layer];
@@ -616,10 +619,11 @@ int moe_cache_set_profiling(moe_cache_t* c, int32_t enabled) {
   if (enabled && c->prof.empty()) {
     c->prof.resize(kProfSlots);
     c->cprof.resize(kProfSlots);
-    for (auto& p : c->prof) {
-      HIPCHK(hipEventCreate(&p.e0)); HIPCHK(hipEventCreate(&p.e1));
-      HIPCHK(hipEventCreate(&p.e2)); HIPCHK(hipEventCreate(&p.e3));
-    }
+    for (auto& p : c->prof)
+      for (KernelEvents* ke : {&p.route, &p.gate_up, &p.down}) {
+        HIPCHK(hipEventCreate(&ke->start));
+        HIPCHK(hipEventCreate(&ke->stop));
+      }
     for (auto& p : c->cprof) { HIPCHK(hipEventCreate(&p.c0)); HIPCHK(hipEventCreate(&p.c1)); }
   }
   c->profiling = enabled != 0;

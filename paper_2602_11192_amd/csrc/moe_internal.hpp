@@ -1,6 +1,7 @@
 // Internal declarations shared by the host runtime and the kernel files.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "moe_cache.h"
@@ -17,7 +18,6 @@ struct LayerState {
   int32_t* expert_in;     // [C] expert held by the slot, -1 = empty (slots fill in index order)
   uint64_t* tick;         // [C] value of the layer clock at the slot's last use
   int32_t* buf_of_slot;   // [C]
-  int32_t* slot_of;       // [E] slot holding the expert, -1 = not resident
   int32_t* free_buf;      // [P] stack of unused buffers
   int32_t* zombie;        // [P] buffers released by the previous call, reusable from the next call on
   uint32_t* used_stamp;   // [P] call sequence number of the buffer's last use
@@ -80,16 +80,45 @@ struct FfnArgs {
   int32_t pass;            // 0: groups whose buffer was resident, 1: groups fetched by this call, 2: all
 };
 
-size_t cache_kernel_lds_bytes(const CacheCallArgs& a);
+// Router inputs of one call.
+struct RouteArgs {
+  const void* x;          // [B][d]
+  const void* router_w;   // [E][d] of this layer
+  const float* bias;      // [B][E] or null
+  int32_t d, norm_topk;
+  int32_t* user_idx;      // optional copies of the routing result for the caller
+  float* user_w;
+  int32_t* arrive;        // [1] workgroup arrival counter, zero between launches
+};
 
-hipError_t launch_route(hipStream_t s, int dtype, const void* x, const void* router_w, const float* bias,
-                        int B, int E, int K, int KS, int d, int norm_topk, int32_t* idx, float* wpair,
-                        int32_t* user_idx, float* user_w);
-hipError_t launch_cache(hipStream_t s, const LayerState& st, const CallTables& t, const CacheCallArgs& a);
+// Pairs (token, expert) of a call are staged in LDS up to this many; larger calls use global scratch.
+constexpr size_t kStageMaxPairs = 2048;
+
+// Optional HIP events bracketing single kernels (attached to the dispatch packets themselves).
+struct KernelEvents {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+
+size_t route_cache_lds_bytes(int E, int C, int P, int n_shared, int B, int K, int KS);
+
+hipError_t launch_route_cache(hipStream_t s, int dtype, const RouteArgs& r, const LayerState& st, const CallTables& t,
+                              const CacheCallArgs& a, KernelEvents ev);
+hipError_t launch_pin(hipStream_t s, const LayerState& st, const CallTables& t, const CacheCallArgs& a);
 hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace);
-hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, hipEvent_t ev_mid);
-hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, hipEvent_t ev_mid);
+hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
+hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 hipError_t launch_combine(hipStream_t s, int dtype, const float* o, const float* wpair, const int32_t* pos_of,
                           int B, int KS, int d, void* y);
+
+// Launch with the events (if any) attached to the kernel's own dispatch, so that
+// hipEventElapsedTime(start, stop) is the kernel's execution time.
+template <typename... Args>
+inline void launch_timed(void (*kernel)(Args...), dim3 grid, dim3 block, size_t lds, hipStream_t s, KernelEvents ev,
+                         Args... args) {
+  if (ev.start && ev.stop)
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, s, ev.start, ev.stop, 0, args...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+}
 
 }  // namespace moe

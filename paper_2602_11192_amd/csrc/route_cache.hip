@@ -1,0 +1,766 @@
+// Router GEMV + softmax/Top-K gating + expert-cache lookup in ONE launch.
+//
+// Paper section 2: Eq. 1 (p = softmax(W_r x), r = Top-K(p)) and the gate
+// weights of Eq. 2; then the offloading runtime of section 2 ("Expert
+// Offloading Systems") and section 3.2: a selected expert that is not resident
+// is fetched on demand and a cached expert is evicted as the policy dictates.
+// LRU is the gamma -> 0+ member and LFU the gamma = 1 member of the
+// discounted-count family of Definition C.1; contents change lazily, only by
+// inserting the requested expert (Remark after Definition C.1).
+//
+// Shape of the launch: one workgroup per token.
+//   phase 1: the waves of the workgroup split the E router rows; each wave forms
+//     whole dot products W_r[e,:].x for up to four rows at a time with every
+//     16-byte load issued up front, then DPP reductions.  Logits stay in LDS.
+//   phase 2: wave 0 owns the token: Top-K by K rounds of wave arg-max on the
+//     logits (ties to the lower id; the same set as Top-K of p), softmax with
+//     wave reductions, gate weights, outputs in ascending expert id.
+//   phase 3 (the only workgroup, or for a batch the one that arrives last at a
+//     device-scope counter - nobody waits): ONE wave runs the B*K lookups in
+//     order, since each one changes the state the next one sees.  For the
+//     usual sizes (LRU, at most 64 slots/buffers/pairs) the whole table lives
+//     in registers, one slot per lane, and a lookup is a ballot plus a DPP
+//     arg-min; otherwise the table is staged in LDS.  The wave also groups the
+//     (token, expert) pairs by expert buffer for the FFN kernels and leaves the
+//     miss list in pinned host memory for the copy scheduler.
+// Nothing is committed when the call runs out of spare buffers, so a failed call
+// leaves the cache unchanged.
+#include "device_utils.hpp"
+#include "moe_internal.hpp"
+
+namespace moe {
+
+#ifdef MOE_PHASE_TIMING
+// Development aid: 100 MHz timestamps of the phases of the last workgroup.
+__device__ long long g_phase_ts[16];
+#define PHASE_TS(i) do { if (threadIdx.x == 0) g_phase_ts[i] = wall_clock64(); } while (0)
+extern "C" int moe_debug_phase_ts(long long* out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_ts), sizeof(long long) * 16);
+}
+#else
+#define PHASE_TS(i) do { } while (0)
+#endif
+
+namespace {
+
+// ---------------------------------------------------------------- dot products
+template <typename T> struct Vec;
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  using type = float4;
+  static __device__ __forceinline__ float dot(const float4& a, const float4& b, float acc) {
+    acc = fmaf(a.x, b.x, acc); acc = fmaf(a.y, b.y, acc);
+    acc = fmaf(a.z, b.z, acc); acc = fmaf(a.w, b.w, acc);
+    return acc;
+  }
+};
+template <> struct Vec<uint16_t> {
+  static constexpr int N = 8;
+  using type = uint4;
+  static __device__ __forceinline__ float dot(const uint4& a, const uint4& b, float acc) {
+    const uint32_t av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc = fmaf(__builtin_bit_cast(float, av[i] << 16), __builtin_bit_cast(float, bv[i] << 16), acc);
+      acc = fmaf(__builtin_bit_cast(float, av[i] & 0xffff0000u),
+                 __builtin_bit_cast(float, bv[i] & 0xffff0000u), acc);
+    }
+    return acc;
+  }
+};
+
+// ordering point between the lanes of ONE wave (LDS and global), no s_barrier
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+  __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ int readlane_i(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+
+// ---------------------------------------------------------------- LDS layout
+struct LdsLayout {
+  size_t tick, score, expert_in, buf_of_slot, slot_of, free_buf, zombie, used, filled, pending, count, start,
+      logit, idx_stage, pair_stage, total;
+};
+
+__host__ __device__ inline bool stage_in_lds(int B, int KS) { return (size_t)B * KS <= kStageMaxPairs; }
+
+__host__ __device__ inline bool fast_table(int policy, int C, int P, int n_pairs) {
+  return policy == MOE_POLICY_LRU && C <= kWave && P <= kWave && n_pairs <= kWave;
+}
+
+__host__ __device__ inline LdsLayout lds_layout(int E, int C, int P, int n_shared, int B, int K, int KS) {
+  LdsLayout l;
+  size_t o = 0;
+  l.tick = o; o += (size_t)C * 8;
+  l.score = o; o += (size_t)E * 8;
+  l.expert_in = o; o += (size_t)C * 4;
+  l.buf_of_slot = o; o += (size_t)C * 4;
+  l.slot_of = o; o += (size_t)E * 4;
+  l.free_buf = o; o += (size_t)P * 4;
+  l.zombie = o; o += (size_t)P * 4;
+  l.used = o; o += (size_t)P * 4;
+  l.filled = o; o += (size_t)P * 4;
+  l.pending = o; o += (size_t)E * 4;
+  l.count = o; o += (size_t)(P + n_shared) * 4;
+  l.start = o; o += (size_t)(P + n_shared) * 4;
+  l.logit = o; o += (size_t)E * 4;
+  const bool stage = stage_in_lds(B, KS);
+  l.idx_stage = o; o += stage ? (size_t)B * K * 4 : 0;
+  l.pair_stage = o; o += stage ? (size_t)B * KS * 4 : 0;
+  l.total = o;
+  return l;
+}
+
+// ---------------------------------------------------------------- phase 2
+// One wave gates one token from the logits in LDS (zs[E]).
+template <int EPL>
+__device__ __forceinline__ void gate_token(const float* zs, int b, int E, int K, int KS, int norm_topk,
+                                           int32_t* idx_g, float* wpair_g, int32_t* user_idx, float* user_w,
+                                           int32_t* idx_stage) {
+  const int lane = threadIdx.x & 63;
+  float z[EPL];
+  bool sel[EPL];
+  float zmax = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int e = lane + i * kWave;
+    z[i] = e < E ? zs[e] : -INFINITY;
+    sel[i] = false;
+    zmax = fmaxf(zmax, z[i]);
+  }
+  zmax = wave_max(zmax);
+  if (K <= 16) {
+    // K rounds of arg-max; a taken entry is masked out; ties resolve to the lowest id
+    float zc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) zc[i] = z[i];
+    for (int k = 0; k < K; ++k) {
+      float m = zc[0];
+#pragma unroll
+      for (int i = 1; i < EPL; ++i) m = fmaxf(m, zc[i]);
+      m = wave_max(m);
+      bool done = false;
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        const uint64_t cand = __ballot(zc[i] == m && (lane + i * kWave) < E);
+        if (!done && cand != 0) {          // uniform
+          const int first = __ffsll((unsigned long long)cand) - 1;
+          if (lane == first) { sel[i] = true; zc[i] = -INFINITY; }
+          done = true;
+        }
+      }
+    }
+  } else {
+    // rank every logit against all others (ties to the lower id)
+    int rank[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) rank[i] = 0;
+    for (int j = 0; j < E; ++j) {
+      const float zj = zs[j];  // same address in every lane: LDS broadcast
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        const int e = lane + i * kWave;
+        rank[i] += (zj > z[i] || (zj == z[i] && j < e)) ? 1 : 0;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) sel[i] = (lane + i * kWave) < E && rank[i] < K;
+  }
+  float p[EPL];
+  float psum = 0.f;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    p[i] = (lane + i * kWave) < E ? expf(z[i] - zmax) : 0.f;
+    psum += p[i];
+  }
+  psum = wave_sum(psum);
+  float selsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    p[i] = p[i] / psum;
+    selsum += sel[i] ? p[i] : 0.f;
+  }
+  selsum = wave_sum(selsum);
+  int base = 0;
+#pragma unroll
+  for (int i = 0; i < EPL; ++i) {
+    const int e = lane + i * kWave;
+    const uint64_t m = __ballot(sel[i]);
+    if (sel[i]) {
+      const int pos = base + __popcll(m & ((1ull << lane) - 1ull));   // ascending expert id
+      const float w = norm_topk ? p[i] / selsum : p[i];
+      idx_g[(size_t)b * K + pos] = e;
+      wpair_g[(size_t)b * KS + pos] = w;
+      if (idx_stage) idx_stage[(size_t)b * K + pos] = e;
+      if (user_idx) user_idx[(size_t)b * K + pos] = e;
+      if (user_w) user_w[(size_t)b * K + pos] = w;
+    }
+    base += __popcll(m);
+  }
+  if (lane < KS - K) wpair_g[(size_t)b * KS + K + lane] = 1.0f;  // shared experts: weight 1
+}
+
+// ---------------------------------------------------------------- phase 3
+// General path (any C, P, batch; both policies): the table lives in LDS.
+// Runs in ONE wave.  idx: selected experts [B][K] (LDS or global); pair_buf: scratch [B*KS].
+__device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, const int32_t* idx, int32_t* pair_buf,
+                            const LayerState& st, const CallTables& t, const CacheCallArgs& a) {
+  uint64_t* tick = reinterpret_cast<uint64_t*>(smem + L.tick);
+  double* score = reinterpret_cast<double*>(smem + L.score);
+  int32_t* expert_in = reinterpret_cast<int32_t*>(smem + L.expert_in);
+  int32_t* buf_of_slot = reinterpret_cast<int32_t*>(smem + L.buf_of_slot);
+  int32_t* slot_of = reinterpret_cast<int32_t*>(smem + L.slot_of);
+  int32_t* free_buf = reinterpret_cast<int32_t*>(smem + L.free_buf);
+  int32_t* zombie = reinterpret_cast<int32_t*>(smem + L.zombie);
+  uint32_t* used = reinterpret_cast<uint32_t*>(smem + L.used);
+  int32_t* filled = reinterpret_cast<int32_t*>(smem + L.filled);
+  int32_t* pending = reinterpret_cast<int32_t*>(smem + L.pending);
+  int32_t* count = reinterpret_cast<int32_t*>(smem + L.count);
+  int32_t* start = reinterpret_cast<int32_t*>(smem + L.start);
+
+  const int lane = threadIdx.x & 63;
+  const int E = a.E, C = a.C, P = a.P, K = a.K, KS = a.KS;
+  const bool gamma_policy = a.policy == MOE_POLICY_GAMMA;
+
+  // ---- load the table (independent loads, one round trip) ----
+  int64_t clock = st.scalars[SC_CLOCK];
+  int n_res = (int)st.scalars[SC_NRES];
+  int n_free = (int)st.scalars[SC_NFREE];
+  int n_zombie = (int)st.scalars[SC_NZOMBIE];
+  const int64_t trace_n = st.scalars[SC_TRACE_N];
+  for (int s = lane; s < C; s += kWave) {
+    tick[s] = st.tick[s]; expert_in[s] = st.expert_in[s]; buf_of_slot[s] = st.buf_of_slot[s];
+  }
+  for (int e = lane; e < E; e += kWave) {
+    slot_of[e] = -1; pending[e] = 0;
+    if (gamma_policy) score[e] = st.score[e];
+  }
+  for (int i = lane; i < P; i += kWave) {
+    used[i] = st.used_stamp[i]; filled[i] = 0;
+    // free stack, then the buffers the previous call released (all its kernels have finished)
+    if (i < n_free) free_buf[i] = st.free_buf[i];
+    else if (i < n_free + n_zombie) free_buf[i] = st.zombie[i - n_free];
+  }
+  n_free += n_zombie;
+  n_zombie = 0;
+  wave_sync();
+  for (int s = lane; s < C; s += kWave)       // expert -> slot index, rebuilt from the slots
+    if (expert_in[s] >= 0) slot_of[expert_in[s]] = s;
+  wave_sync();
+  PHASE_TS(4);
+
+  const uint32_t seq = a.seq;
+  const int n_lookups = a.mode == 0 ? a.B * K : K;
+  int status = MOE_OK, n_miss = 0, n_evict = 0, n_hits = 0;
+  int64_t trace_added = 0;
+
+  for (int q = 0; q < n_lookups; ++q) {
+    const int b = a.mode == 0 ? q / K : 0;
+    const int k = a.mode == 0 ? q % K : q;
+    const int e = a.mode == 0 ? idx[q] : a.pin_ids[q];
+    int s = slot_of[e];
+    int evicted = -1, buf;
+    const bool hit = s >= 0;
+    if (hit) {
+      buf = buf_of_slot[s];
+      ++n_hits;
+    } else {
+      if (n_res < C) {            // slots fill in index order, so the lowest empty slot is n_res
+        s = n_res;
+        buf = free_buf[n_free - 1];
+        --n_free;
+        ++n_res;
+      } else {
+        int vs = -1;
+        uint64_t vt = ~0ull;
+        double vsc = 0.0;
+        for (int c = lane; c < C; c += kWave) {
+          const uint64_t tc = tick[c];
+          if (!gamma_policy) {
+            if (tc < vt) { vt = tc; vs = c; }
+          } else {
+            const int ex = expert_in[c];
+            if (pending[ex]) continue;     // wanted by the current token: never a victim
+            const double sc = score[ex];
+            if (vs < 0 || sc < vsc || (sc == vsc && tc < vt)) { vsc = sc; vt = tc; vs = c; }
+          }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+          const int os = __shfl_xor(vs, off);
+          const uint64_t ot = __shfl_xor((unsigned long long)vt, off);
+          const double osc = __shfl_xor(vsc, off);
+          bool take;
+          if (os < 0) take = false;
+          else if (vs < 0) take = true;
+          else if (!gamma_policy) take = ot < vt;
+          else take = osc < vsc || (osc == vsc && ot < vt);
+          if (take) { vs = os; vt = ot; vsc = osc; }
+        }
+        s = vs;
+        evicted = expert_in[s];
+        const int vb = buf_of_slot[s];
+        if (used[vb] == seq) {    // an earlier token of this call reads that buffer: leave it intact
+          if (n_free == 0) { status = MOE_ERR_STAGING_EXHAUSTED; break; }
+          buf = free_buf[n_free - 1];
+          --n_free;
+          if (lane == 0) zombie[n_zombie] = vb;
+          ++n_zombie;
+        } else {
+          buf = vb;
+        }
+        ++n_evict;
+      }
+      if (lane == 0) {
+        if (evicted >= 0) slot_of[evicted] = -1;
+        expert_in[s] = e;
+        slot_of[e] = s;
+        buf_of_slot[s] = buf;
+        filled[buf] = 1;
+        if (n_miss < a.max_miss) a.miss_list[n_miss] = MissEntry{e, buf};
+      }
+      ++n_miss;
+    }
+    ++clock;
+    if (lane == 0) {
+      tick[s] = (uint64_t)clock;
+      used[buf] = seq;
+      pending[e] = 1;
+      if (a.mode == 0) {
+        pair_buf[(size_t)b * KS + k] = buf;
+        if (trace_n + trace_added < a.trace_cap)
+          st.trace[trace_n + trace_added] = moe_trace_rec_t{b, e, hit ? 1 : 0, evicted};
+      }
+    }
+    if (a.mode == 0) ++trace_added;
+    wave_sync();
+    // Definition C.1: the discounted counts advance once per token (each pinned expert is a token)
+    if (gamma_policy && (a.mode == 1 || k == K - 1)) {
+      for (int x = lane; x < E; x += kWave) {
+        score[x] = __dadd_rn(__dmul_rn(a.gamma, score[x]), (double)pending[x]);
+        pending[x] = 0;
+      }
+      wave_sync();
+    }
+  }
+
+  PHASE_TS(5);
+  int n_groups = 0;
+  if (status == MOE_OK && a.mode == 0) {
+    // ---- group the (token, expert) pairs by the buffer they read: stable counting sort ----
+    const int NP = a.B * KS;
+    const int NB = P + a.n_shared;
+    for (int p = lane; p < a.B * a.n_shared; p += kWave) {
+      const int b = p / a.n_shared, sidx = p % a.n_shared;
+      pair_buf[(size_t)b * KS + K + sidx] = P + sidx;
+    }
+    for (int i = lane; i < NB; i += kWave) count[i] = 0;
+    wave_sync();
+    for (int p = lane; p < NP; p += kWave) atomicAdd(&count[pair_buf[p]], 1);
+    wave_sync();
+    if (lane == 0) {
+      int off = 0;
+      for (int id = 0; id < NB; ++id) {
+        const int c = count[id];
+        if (c > 0) {
+          t.grp_buf[n_groups] = id;
+          t.grp_begin[n_groups] = off;
+          t.grp_count[n_groups] = c;
+          t.grp_miss[n_groups] = id < P ? filled[id] : 0;
+          ++n_groups;
+        }
+        start[id] = off;
+        off += c;
+      }
+      for (int p = 0; p < NP; ++p) {
+        const int pos = start[pair_buf[p]]++;
+        t.sorted_pair[pos] = p;
+        t.pos_of[p] = pos;
+      }
+    }
+    n_groups = __shfl(n_groups, 0);
+  }
+  if (a.mode == 0 && lane == 0) *t.n_groups = n_groups;
+  PHASE_TS(6);
+
+  if (status == MOE_OK) {
+    // ---- commit ----
+    wave_sync();
+    for (int s = lane; s < C; s += kWave) {
+      st.tick[s] = tick[s]; st.expert_in[s] = expert_in[s]; st.buf_of_slot[s] = buf_of_slot[s];
+    }
+    if (gamma_policy)
+      for (int e = lane; e < E; e += kWave) st.score[e] = score[e];
+    for (int i = lane; i < n_free; i += kWave) st.free_buf[i] = free_buf[i];
+    for (int i = lane; i < n_zombie; i += kWave) st.zombie[i] = zombie[i];
+    for (int i = lane; i < P; i += kWave) st.used_stamp[i] = used[i];
+    if (lane == 0) {
+      st.scalars[SC_CLOCK] = clock;
+      st.scalars[SC_NRES] = n_res;
+      st.scalars[SC_NFREE] = n_free;
+      st.scalars[SC_NZOMBIE] = n_zombie;
+      st.scalars[SC_CALLSEQ] = seq;
+      st.scalars[SC_TRACE_N] = trace_n + trace_added;
+    }
+  }
+  PHASE_TS(7);
+  if (lane == 0) {
+    Mailbox* mb = a.mailbox;
+    mb->status = status;
+    mb->n_miss = n_miss;
+    mb->n_evict = n_evict;
+    mb->n_groups = n_groups;
+    mb->n_hits = n_hits;
+    mb->seq = seq;   // read by the host only after the kernel has completed
+  }
+  PHASE_TS(8);
+}
+
+// ---------------------------------------------------------------- phase 3, register path
+// LRU with at most 64 slots, 64 buffers and 64 (token, expert) pairs: lane s holds
+// slot s (expert, last-use tick, buffer), lane p holds buffer p's use stamp, lane i
+// holds entry i of the free and released-buffer stacks, lane q holds pair q.
+struct FastTable {
+  int exp, buf, free_b, zomb;
+  uint64_t tick;
+  uint32_t used;
+  int64_t clock, trace_n;
+  int n_res, n_free, n_zombie;
+};
+
+__device__ __forceinline__ FastTable fast_load(const LayerState& st, int C, int P) {
+  const int lane = threadIdx.x & 63;
+  FastTable f;
+  f.clock = st.scalars[SC_CLOCK];
+  f.n_res = (int)st.scalars[SC_NRES];
+  f.n_free = (int)st.scalars[SC_NFREE];
+  f.n_zombie = (int)st.scalars[SC_NZOMBIE];
+  f.trace_n = st.scalars[SC_TRACE_N];
+  f.exp = lane < C ? st.expert_in[lane] : -2;
+  f.tick = lane < C ? st.tick[lane] : ~0ull;
+  f.buf = lane < C ? st.buf_of_slot[lane] : -1;
+  f.used = lane < P ? st.used_stamp[lane] : 0u;
+  f.free_b = lane < P ? st.free_buf[lane] : -1;
+  f.zomb = lane < P ? st.zombie[lane] : -1;
+  return f;
+}
+
+// index of the lane (< C) holding the smallest tick; ticks of valid lanes are unique
+__device__ __forceinline__ int wave_argmin_tick(uint64_t tick) {
+  uint32_t hi = (uint32_t)(tick >> 32), lo = (uint32_t)tick;
+#define MOE_MIN_STEP(CTRL)                                                                              \
+  {                                                                                                     \
+    const uint32_t ohi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi, CTRL, 0xf, 0xf, true);       \
+    const uint32_t olo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, CTRL, 0xf, 0xf, true);       \
+    const bool less = ohi < hi || (ohi == hi && olo < lo);                                              \
+    hi = less ? ohi : hi;                                                                               \
+    lo = less ? olo : lo;                                                                               \
+  }
+  MOE_MIN_STEP(0xB1) MOE_MIN_STEP(0x4E) MOE_MIN_STEP(0x141) MOE_MIN_STEP(0x140)
+#undef MOE_MIN_STEP
+  uint64_t best = ~0ull;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const uint64_t v = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, r * 16) << 32) |
+                       (uint32_t)__builtin_amdgcn_readlane((int)lo, r * 16);
+    best = v < best ? v : best;
+  }
+  return __ffsll((unsigned long long)__ballot(tick == best)) - 1;
+}
+
+// Runs in ONE wave.  my_e: lane q < n_lookups holds the expert of lookup q (decode:
+// q = b*K + k; pin: q = list position).
+__device__ void cache_phase_fast(FastTable f, int my_e, const LayerState& st, const CallTables& t,
+                                 const CacheCallArgs& a) {
+  const int lane = threadIdx.x & 63;
+  const int C = a.C, P = a.P, K = a.K, KS = a.KS;
+  // buffers released by the previous call: all its kernels have finished, reuse them
+  {
+    const int src = lane - f.n_free;
+    const int z = __shfl(f.zomb, src < 0 ? 0 : src);
+    if (src >= 0 && src < f.n_zombie) f.free_b = z;
+    f.n_free += f.n_zombie;
+    f.n_zombie = 0;
+  }
+  const uint32_t seq = a.seq;
+  const int n_lookups = a.mode == 0 ? a.B * K : K;
+  int status = MOE_OK, n_miss = 0, n_evict = 0, n_hits = 0;
+  int my_pair = -1;       // lane p = b*KS + k: buffer the pair reads
+  bool filled = false;    // lane p: buffer p is being filled by this call
+  PHASE_TS(4);
+
+  for (int q = 0; q < n_lookups; ++q) {
+    const int e = readlane_i(my_e, q);
+    const uint64_t hm = __ballot(f.exp == e);
+    int s, buf, evicted = -1;
+    const bool hit = hm != 0;
+    if (hit) {
+      s = __ffsll((unsigned long long)hm) - 1;
+      buf = readlane_i(f.buf, s);
+      ++n_hits;
+    } else {
+      if (f.n_res < C) {          // slots fill in index order, so the lowest empty slot is n_res
+        s = f.n_res++;
+        buf = readlane_i(f.free_b, --f.n_free);
+      } else {
+        s = wave_argmin_tick(f.tick);
+        evicted = readlane_i(f.exp, s);
+        const int vb = readlane_i(f.buf, s);
+        if ((uint32_t)readlane_i((int)f.used, vb) == seq) {   // an earlier token of this call reads it
+          if (f.n_free == 0) { status = MOE_ERR_STAGING_EXHAUSTED; break; }
+          buf = readlane_i(f.free_b, --f.n_free);
+          if (lane == f.n_zombie) f.zomb = vb;
+          ++f.n_zombie;
+        } else {
+          buf = vb;
+        }
+        ++n_evict;
+      }
+      if (lane == s) { f.exp = e; f.buf = buf; }
+      if (lane == buf) filled = true;
+      if (lane == 0 && n_miss < a.max_miss) a.miss_list[n_miss] = MissEntry{e, buf};
+      ++n_miss;
+    }
+    ++f.clock;
+    if (lane == s) f.tick = (uint64_t)f.clock;
+    if (lane == buf) f.used = seq;
+    if (a.mode == 0) {
+      const int b = q / K, k = q - b * K;
+      if (lane == b * KS + k) my_pair = buf;
+      if (lane == 0 && f.trace_n + q < a.trace_cap)
+        st.trace[f.trace_n + q] = moe_trace_rec_t{b, e, hit ? 1 : 0, evicted};
+    }
+  }
+  PHASE_TS(5);
+
+  int n_groups = 0;
+  if (status == MOE_OK && a.mode == 0) {
+    // ---- group the pairs by buffer: rank every pair against all others (stable) ----
+    const int NP = a.B * KS;
+    {
+      const int b = lane / KS, k = lane - b * KS;
+      if (lane < NP && k >= K) my_pair = P + (k - K);     // shared experts
+    }
+    int rank = 0, same_before = 0, cnt = 0;
+    for (int q = 0; q < NP; ++q) {
+      const int bq = readlane_i(my_pair, q);
+      rank += (bq < my_pair || (bq == my_pair && q < lane)) ? 1 : 0;
+      cnt += bq == my_pair ? 1 : 0;
+      same_before += (bq == my_pair && q < lane) ? 1 : 0;
+    }
+    const bool is_first = lane < NP && same_before == 0;
+    const uint64_t fm = __ballot(is_first);
+    int gidx = 0;
+    for (uint64_t m = fm; m != 0; m &= m - 1) {
+      const int q = __ffsll((unsigned long long)m) - 1;
+      gidx += readlane_i(my_pair, q) < my_pair ? 1 : 0;
+    }
+    const int was_filled = __shfl((int)filled, my_pair < P && my_pair >= 0 ? my_pair : 0);
+    if (lane < NP) {
+      t.sorted_pair[rank] = lane;
+      t.pos_of[lane] = rank;
+      if (is_first) {
+        t.grp_buf[gidx] = my_pair;
+        t.grp_begin[gidx] = rank;
+        t.grp_count[gidx] = cnt;
+        t.grp_miss[gidx] = my_pair < P ? was_filled : 0;
+      }
+    }
+    n_groups = __popcll(fm);
+  }
+  if (a.mode == 0 && lane == 0) *t.n_groups = n_groups;
+  PHASE_TS(6);
+
+  if (status == MOE_OK) {
+    // ---- commit ----
+    if (lane < C) { st.tick[lane] = f.tick; st.expert_in[lane] = f.exp; st.buf_of_slot[lane] = f.buf; }
+    if (lane < P) { st.used_stamp[lane] = f.used; st.free_buf[lane] = f.free_b; st.zombie[lane] = f.zomb; }
+    if (lane == 0) {
+      st.scalars[SC_CLOCK] = f.clock;
+      st.scalars[SC_NRES] = f.n_res;
+      st.scalars[SC_NFREE] = f.n_free;
+      st.scalars[SC_NZOMBIE] = f.n_zombie;
+      st.scalars[SC_CALLSEQ] = seq;
+      st.scalars[SC_TRACE_N] = f.trace_n + (a.mode == 0 ? n_lookups : 0);
+    }
+  }
+  PHASE_TS(7);
+  if (lane == 0) {
+    Mailbox* mb = a.mailbox;
+    mb->status = status;
+    mb->n_miss = n_miss;
+    mb->n_evict = n_evict;
+    mb->n_groups = n_groups;
+    mb->n_hits = n_hits;
+    mb->seq = seq;   // read by the host only after the kernel has completed
+  }
+  PHASE_TS(8);
+}
+
+// ---------------------------------------------------------------- the decode launch
+template <typename T>
+__global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerState st, CallTables t, CacheCallArgs a) {
+  extern __shared__ __align__(8) unsigned char smem[];
+  __shared__ int s_last;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int n_waves = blockDim.x >> 6;
+  const int b = blockIdx.x;
+  const int E = a.E, K = a.K, KS = a.KS, d = r.d;
+  const bool single = gridDim.x == 1;
+  const bool fast = fast_table(a.policy, a.C, a.P, a.B * KS);
+  PHASE_TS(0);
+
+  // With one workgroup the cache table can be fetched while the router GEMV runs.
+  FastTable ft{};
+  if (single && fast && wave == 0) ft = fast_load(st, a.C, a.P);
+
+  const LdsLayout L = lds_layout(E, a.C, a.P, a.n_shared, a.B, K, KS);
+  float* zs = reinterpret_cast<float*>(smem + L.logit);
+  const bool stage = stage_in_lds(a.B, KS);
+  int32_t* idx_stage = stage ? reinterpret_cast<int32_t*>(smem + L.idx_stage) : nullptr;
+  int32_t* pair_stage = stage ? reinterpret_cast<int32_t*>(smem + L.pair_stage) : t.pair_buf;
+
+  // ---- phase 1: router rows of token b, four rows per wave at a time ----
+  {
+    using V = Vec<T>;
+    constexpr int EB = 4;
+    const int n_vec = d / V::N;  // host guarantees d % V::N == 0
+    const typename V::type* xv = reinterpret_cast<const typename V::type*>(static_cast<const T*>(r.x) + (size_t)b * d);
+    const typename V::type* wbase = reinterpret_cast<const typename V::type*>(r.router_w);
+    for (int e0 = wave; e0 < E; e0 += n_waves * EB) {
+      const typename V::type* wv[EB];
+#pragma unroll
+      for (int j = 0; j < EB; ++j) {
+        const int e = e0 + j * n_waves;
+        wv[j] = wbase + (size_t)(e < E ? e : E - 1) * n_vec;   // clamped: loads stay unconditional
+      }
+      float acc[EB] = {0.f, 0.f, 0.f, 0.f};
+      constexpr int CB = 4;   // chunks per lane fetched together: (1 + EB) * CB loads in flight
+      for (int c0 = lane; c0 < n_vec; c0 += kWave * CB) {
+        typename V::type xc[CB], wc[EB][CB];
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+          const int c = c0 + i * kWave;
+          const int cc = c < n_vec ? c : n_vec - 1;     // clamped: in bounds, masked below
+          xc[i] = xv[cc];
+#pragma unroll
+          for (int j = 0; j < EB; ++j) wc[j][i] = wv[j][cc];
+        }
+#pragma unroll
+        for (int i = 0; i < CB; ++i) {
+          if (c0 + i * kWave < n_vec) {
+#pragma unroll
+            for (int j = 0; j < EB; ++j) acc[j] = V::dot(wc[j][i], xc[i], acc[j]);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < EB; ++j) {
+        const int e = e0 + j * n_waves;
+        const float s = wave_sum(acc[j]);
+        if (lane == 0 && e < E) zs[e] = s + (r.bias ? r.bias[(size_t)b * E + e] : 0.f);
+      }
+    }
+  }
+  __syncthreads();
+  PHASE_TS(1);
+
+  // ---- phase 2: gating of token b by wave 0 ----
+  if (wave != 0) return;
+  if (E <= 64) gate_token<1>(zs, b, E, K, KS, r.norm_topk, t.idx, t.wpair, r.user_idx, r.user_w, idx_stage);
+  else if (E <= 256) gate_token<4>(zs, b, E, K, KS, r.norm_topk, t.idx, t.wpair, r.user_idx, r.user_w, idx_stage);
+  else gate_token<16>(zs, b, E, K, KS, r.norm_topk, t.idx, t.wpair, r.user_idx, r.user_w, idx_stage);
+  PHASE_TS(2);
+
+  if (!single) {
+    // ---- the last workgroup to arrive carries on (no waiting anywhere) ----
+    if (lane == 0) {
+      __threadfence();
+      s_last = atomicAdd(r.arrive, 1) == (int)gridDim.x - 1;
+    }
+    wave_sync();
+    if (!s_last) return;
+    if (lane == 0) *r.arrive = 0;   // ready for the next launch on this stream
+    __threadfence();
+    // routing results of the other workgroups: read at device scope
+    if (stage)
+      for (int i = lane; i < a.B * K; i += kWave)
+        idx_stage[i] = __hip_atomic_load(&t.idx[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (fast) ft = fast_load(st, a.C, a.P);
+  }
+  wave_sync();
+  PHASE_TS(3);
+
+  // ---- phase 3: cache lookups, one wave ----
+  if (fast) {
+    const int n_lookups = a.B * K;
+    const int my_e = lane < n_lookups ? idx_stage[lane] : -1;
+    cache_phase_fast(ft, my_e, st, t, a);
+  } else {
+    cache_phase_general(smem, L, stage ? idx_stage : t.idx, pair_stage, st, t, a);
+  }
+}
+
+__global__ void __launch_bounds__(64) pin_kernel(LayerState st, CallTables t, CacheCallArgs a) {
+  extern __shared__ __align__(8) unsigned char smem[];
+  const int lane = threadIdx.x;
+  if (fast_table(a.policy, a.C, a.P, a.K)) {
+    const int my_e = lane < a.K ? a.pin_ids[lane] : -1;
+    cache_phase_fast(fast_load(st, a.C, a.P), my_e, st, t, a);
+  } else {
+    const LdsLayout L = lds_layout(a.E, a.C, a.P, a.n_shared, 1, a.K, a.KS);
+    cache_phase_general(smem, L, nullptr, nullptr, st, t, a);
+  }
+}
+
+__global__ void reset_kernel(LayerState st, int E, int C, int P, int clear_trace) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < C) { st.expert_in[i] = -1; st.tick[i] = 0; st.buf_of_slot[i] = -1; }
+  if (i < E) st.score[i] = 0.0;
+  if (i < P) { st.free_buf[i] = P - 1 - i; st.zombie[i] = -1; st.used_stamp[i] = 0; }  // buffer 0 is popped first
+  if (i == 0) {
+    st.scalars[SC_CLOCK] = 0;
+    st.scalars[SC_NRES] = 0;
+    st.scalars[SC_NFREE] = P;
+    st.scalars[SC_NZOMBIE] = 0;
+    if (clear_trace) st.scalars[SC_TRACE_N] = 0;
+  }
+}
+
+}  // namespace
+
+size_t route_cache_lds_bytes(int E, int C, int P, int n_shared, int B, int K, int KS) {
+  return lds_layout(E, C, P, n_shared, B, K, KS).total;
+}
+
+hipError_t launch_route_cache(hipStream_t s, int dtype, const RouteArgs& r, const LayerState& st, const CallTables& t,
+                              const CacheCallArgs& a, KernelEvents ev) {
+  // Few tokens: 16 waves per token so that the router rows stream with many loads
+  // in flight.  Many tokens: the grid supplies the parallelism.
+  int waves = a.B <= 16 ? 16 : 4;
+  if (waves > a.E) waves = a.E;
+  dim3 grid(a.B), block(64 * waves);
+  const size_t lds = route_cache_lds_bytes(a.E, a.C, a.P, a.n_shared, a.B, a.K, a.KS);
+  if (dtype == MOE_DTYPE_FP32)
+    launch_timed(route_cache_kernel<float>, grid, block, lds, s, ev, r, st, t, a);
+  else
+    launch_timed(route_cache_kernel<uint16_t>, grid, block, lds, s, ev, r, st, t, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_pin(hipStream_t s, const LayerState& st, const CallTables& t, const CacheCallArgs& a) {
+  const size_t lds = route_cache_lds_bytes(a.E, a.C, a.P, a.n_shared, 1, a.K, a.KS);
+  hipLaunchKernelGGL(pin_kernel, dim3(1), dim3(64), lds, s, st, t, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace) {
+  int n = E > C ? E : C;
+  n = n > P ? n : P;
+  hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, E, C, P, clear_trace);
+  return hipGetLastError();
+}
+
+}  // namespace moe

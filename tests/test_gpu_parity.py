@@ -106,6 +106,32 @@ def test_small_bf16_batched_with_evictions_inside_a_call(torch, P, tiled, batch)
     cache.close()
 
 
+def test_lru_table_larger_than_a_wave(torch, P):
+    # capacity above 64 slots: the cache table is staged in LDS instead of registers
+    cfg = small_cfg(n_experts=96, capacity=70, n_layers=1, n_seqs=2, n_steps=40, pref_lo=0, pref_hi=0, beta=0.0)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, trace_capacity=4096)
+    ost = OracleStack(wl, keep=96)
+    _, _, traces = run_sequence_serial(wl, cache, ost, torch=torch, pins=False, y_every=10)
+    assert cache.moe_cache_stats(0)["evictions"] > 0
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+def test_alternating_small_and_large_batches_share_one_table(torch, P):
+    # calls of 1-3 tokens use the register-resident table, calls of 17 tokens the LDS one
+    cfg = small_cfg(n_seqs=17, n_steps=8, n_layers=1, capacity=8)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=17, staging_buffers=17 * cfg.top_k, trace_capacity=8192)
+    ost = OracleStack(wl)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        rows = list(range(17)) if step % 2 else [step % 17, (step + 5) % 17, (step + 11) % 17][: 1 + step % 3]
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, rows, step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_staging_exhausted_leaves_cache_unchanged(torch, P):
     from paper_2602_11192_amd import binding as B
     cfg = small_cfg(n_seqs=8, n_steps=4, n_layers=1, capacity=4, pref_lo=0, pref_hi=0, beta=0.0)

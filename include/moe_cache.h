@@ -206,6 +206,19 @@ int moe_cache_set_profiling(moe_cache_t* cache, int32_t enabled);
 /* Read and optionally clear the timing sums; waits for the timed work. */
 int moe_cache_timing(moe_cache_t* cache, moe_timing_t* out, int32_t clear);
 
+/*
+ * Calibration, not part of the decode path: time `iters` launches of a plain
+ * streaming read (mode 0; dst_dev may be NULL) or a plain copy (mode 1) of
+ * `bytes` bytes (a multiple of 16) between device buffers, after one warm-up
+ * launch.  *avg_ms = mean kernel time from HIP events attached to each dispatch.
+ * The read kernel uses the access pattern of the expert kernels (wave-wide
+ * 16-byte loads, all issued before use), so bytes / *avg_ms is the bandwidth the
+ * GPU sustains for that pattern; the copy is the reference dispatch for scaling
+ * profiler memory counters.
+ */
+int moe_probe_stream(void* src_dev, void* dst_dev, uint64_t bytes, int32_t mode, int32_t iters,
+                     void* hip_stream, double* avg_ms);
+
 /* Text of the last error on this thread ("" if none). */
 const char* moe_last_error(void);
 

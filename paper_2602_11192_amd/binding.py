@@ -29,7 +29,8 @@ MOE_LAYOUT_ROWMAJOR, MOE_LAYOUT_TILED = 0, 1
 
 EXPORTS = ["moe_expert_bytes", "moe_pack_expert", "moe_cache_create", "moe_cache_destroy", "moe_cache_reset",
            "moe_cache_prefill_pins", "moe_layer_decode", "moe_cache_stats", "moe_cache_read_trace",
-           "moe_cache_resident", "moe_cache_set_profiling", "moe_cache_timing", "moe_last_error", "moe_version"]
+           "moe_cache_resident", "moe_cache_set_profiling", "moe_cache_timing", "moe_probe_stream",
+           "moe_last_error", "moe_version"]
 
 
 class moe_cache_config_t(C.Structure):
@@ -83,6 +84,7 @@ def _load():
     lib.moe_cache_resident.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.moe_cache_set_profiling.argtypes = [vp, i32]
     lib.moe_cache_timing.argtypes = [vp, C.POINTER(moe_timing_t), i32]
+    lib.moe_probe_stream.argtypes = [vp, vp, C.c_uint64, i32, i32, vp, C.POINTER(C.c_double)]
     lib.moe_last_error.restype = C.c_char_p
     lib.moe_version.restype = C.c_char_p
     for name in EXPORTS:
@@ -116,6 +118,15 @@ def moe_pack_expert(src: np.ndarray, dst: np.ndarray, d_model: int, d_ff: int) -
     assert src.dtype == np.uint16 and dst.dtype == np.uint16
     assert src.size == dst.size == 3 * d_model * d_ff and src.flags.c_contiguous and dst.flags.c_contiguous
     _check(lib.moe_pack_expert(src.ctypes.data, dst.ctypes.data, d_model, d_ff))
+
+
+def moe_probe_stream(src, dst, nbytes: int, mode: int, iters: int = 10, stream=None) -> float:
+    """Average kernel time (ms) of a plain read (mode 0) or copy (mode 1) of nbytes between device tensors."""
+    ms = C.c_double()
+    rc = lib.moe_probe_stream(_ptr(src), _ptr(dst), nbytes, mode, iters, _stream(stream), C.byref(ms))
+    if rc != MOE_OK:
+        raise MoeError(rc, "moe_probe_stream failed")
+    return ms.value
 
 
 def _ptr(t):

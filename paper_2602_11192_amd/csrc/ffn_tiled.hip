@@ -144,7 +144,13 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_tiled_kernel(FfnArgs a) {
 
 hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, KernelEvents e1, KernelEvents e2) {
   if (a.g_max <= 0) return hipSuccess;
-  constexpr int WAVES = 8, CH = 8;
+#ifndef MOE_FFN_WAVES
+#define MOE_FFN_WAVES 8
+#endif
+#ifndef MOE_FFN_CH
+#define MOE_FFN_CH 8
+#endif
+  constexpr int WAVES = MOE_FFN_WAVES, CH = MOE_FFN_CH;
   dim3 block(64 * WAVES);
   dim3 g1(a.f / 16, a.g_max), g2(a.d / 16, a.g_max);
   if (a.max_count <= 16) {

@@ -1,0 +1,134 @@
+"""GPU parity at the full layer shapes of the five workloads.
+
+Routing indices, cache traces, statistics and resident sets are compared for
+every lookup; outputs are compared on a sample of the tokens (the oracle needs
+3*d*d_ff double-precision multiply-adds per expert and token).  Layer stacks are
+cut to one layer here: the layers of a stack are independent problems of the
+same shape, and one layer of the Mixtral-like stack already holds 2.8 GB of
+expert weights."""
+import numpy as np
+import pytest
+
+import oracle
+from tests.helpers import TOL, OracleStack, compare_traces_and_stats, rel_err, run_sequence_serial
+from workload import Workload, get_config, widen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    return t
+
+
+@pytest.fixture(scope="module")
+def P():
+    from paper_2602_11192_amd import pool
+    return pool
+
+
+@pytest.fixture(autouse=True)
+def oracle_threads():
+    oracle.set_threads(16)
+    yield
+    oracle.set_threads(1)
+
+
+@pytest.fixture(scope="module")
+def olmoe(P):
+    wl = Workload(get_config("olmoe_like"))
+    return wl, P.build_pool(wl, tiled=True)
+
+
+def test_olmoe_like_full_workload_sequence_serial(torch, P, olmoe):
+    """The benchmark's configuration: 16 sequences x 128 steps, capacity 16, prefetch per sequence."""
+    wl, pool = olmoe
+    cfg = wl.cfg
+    cache = P.make_cache(wl, pool=pool, trace_capacity=cfg.n_seqs * cfg.n_steps * cfg.top_k)
+    ost = OracleStack(wl, keep=cfg.n_experts)
+    worst, n_y, traces = run_sequence_serial(wl, cache, ost, torch=torch, y_every=16)
+    assert n_y == cfg.n_seqs * cfg.n_steps // 16
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    st = cache.moe_cache_stats()
+    assert st["lookups"] == cfg.n_seqs * cfg.n_steps * cfg.top_k
+    assert 0.7 < st["hits"] / st["lookups"] < 0.95        # the concentrated regime of the fine-tuned models
+    print("olmoe_like: worst rel err %.3e over %d tokens, hit rate %.3f" % (worst, n_y, st["hits"] / st["lookups"]))
+    cache.close()
+
+
+def test_olmoe_like_cold_start_without_prefetch(torch, P, olmoe):
+    wl, pool = olmoe
+    cfg = wl.cfg
+    cache = P.make_cache(wl, pool=pool, trace_capacity=4 * cfg.n_steps * cfg.top_k)
+    ost = OracleStack(wl, keep=cfg.n_experts)
+    _, _, traces = run_sequence_serial(wl, cache, ost, torch=torch, pins=False, y_every=32, seqs=[0, 5, 9, 15])
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+@pytest.mark.parametrize("batch", [16, 5])
+def test_olmoe_like_resident_path_batched(torch, P, olmoe, batch):
+    """Every expert resident (capacity = E), one token of each sequence per call."""
+    wl, pool = olmoe
+    cfg = wl.cfg
+    cache = P.make_cache(wl, pool=pool, capacity=cfg.n_experts, max_batch=batch, trace_capacity=8192)
+    ost = OracleStack(wl, capacity=cfg.n_experts, keep=cfg.n_experts)
+    ids = list(range(cfg.n_experts))
+    cache.moe_cache_prefill_pins(0, ids)
+    ost.caches[0].pin(ids)
+    y = torch.empty((batch, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.empty((batch, cfg.top_k), dtype=torch.int32, device="cuda:0")
+    bias = np.stack([wl.bias(0, s) for s in range(batch)])
+    bias_dev = torch.from_numpy(bias).cuda()
+    trace = []
+    for step in (0, 1, 50, 127):
+        xs = np.stack([wl.tokens(s)[step] for s in range(batch)])
+        cache.moe_layer_decode(0, P.to_device(xs), y, bias_dev, idx)
+        res = ost.decode(0, widen(xs), bias)
+        torch.cuda.synchronize()
+        assert idx.cpu().numpy().tolist() == res.idx.tolist()
+        assert rel_err(P.to_numpy(y), res.y).max() <= TOL["bf16"]
+        trace += res.trace
+    compare_traces_and_stats(cache, ost, [trace], cfg.expert_bytes)
+    assert cache.moe_cache_stats()["misses"] == 0
+    cache.close()
+
+
+@pytest.mark.parametrize("name", ["mixtral_like", "phi35_like_concentrated", "phi35_like_diverse", "deepseek_like"])
+def test_one_layer_of_the_large_stacks(torch, P, name):
+    cfg = get_config(name).with_(n_layers=1, n_seqs=2, n_steps=24)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, trace_capacity=4096)
+    ost = OracleStack(wl, keep=min(cfg.n_experts, 16))
+    worst, n_y, traces = run_sequence_serial(wl, cache, ost, torch=torch, y_every=8)
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    st = cache.moe_cache_stats()
+    print("%s: worst rel err %.3e over %d tokens, hit rate %.3f" % (name, worst, n_y, st["hits"] / st["lookups"]))
+    cache.close()
+
+
+def test_deepseek_like_batched_shared_cache(torch, P):
+    """Eight sequences decode together through one capacity-12 cache with two shared experts."""
+    cfg = get_config("deepseek_like").with_(n_layers=1, n_seqs=8, n_steps=6)
+    wl = Workload(cfg)
+    B = cfg.n_seqs
+    cache = P.make_cache(wl, max_batch=B, staging_buffers=B * cfg.top_k, trace_capacity=4096)
+    ost = OracleStack(wl, keep=cfg.n_experts)
+    y = torch.empty((B, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.empty((B, cfg.top_k), dtype=torch.int32, device="cuda:0")
+    bias = np.stack([wl.bias(0, s) for s in range(B)])
+    bias_dev = torch.from_numpy(bias).cuda()
+    trace = []
+    for step in range(cfg.n_steps):
+        xs = np.stack([wl.tokens(s)[step] for s in range(B)])
+        cache.moe_layer_decode(0, P.to_device(xs), y, bias_dev, idx)
+        res = ost.decode(0, widen(xs), bias, compute_y=step % 3 == 0)
+        torch.cuda.synchronize()
+        assert idx.cpu().numpy().tolist() == res.idx.tolist()
+        if step % 3 == 0:
+            assert rel_err(P.to_numpy(y), res.y).max() <= TOL["bf16"]
+        trace += res.trace
+    compare_traces_and_stats(cache, ost, [trace], cfg.expert_bytes)
+    cache.close()

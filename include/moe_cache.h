@@ -120,10 +120,13 @@ typedef struct {
 
 /* Device-side timing collected while profiling is on (moe_cache_set_profiling). */
 typedef struct {
-  uint64_t ffn_launches; /* decode calls whose expert-FFN kernels were timed                */
-  double ffn_gate_up_ms; /* summed duration of the gate/up (first) FFN kernel               */
-  double ffn_down_ms;    /* summed duration of the down-projection kernel                   */
-  double route_ms;       /* summed duration of the router + cache-lookup kernels            */
+  uint64_t ffn_launches; /* calls without a miss whose two-kernel expert FFN was timed      */
+  double ffn_gate_up_ms; /* summed duration of their gate/up kernel                         */
+  double ffn_down_ms;    /* summed duration of their down-projection kernel                 */
+  uint64_t ffn_fused_launches; /* calls without a miss that used the single-launch decode FFN */
+  double ffn_fused_ms;   /* summed duration of that kernel                                  */
+  uint64_t route_launches; /* router + gating + cache-lookup launches timed                 */
+  double route_ms;       /* their summed duration                                           */
   uint64_t copies;       /* expert copies timed                                             */
   uint64_t copy_bytes;   /* bytes moved by them                                             */
   double copy_ms;        /* summed duration of the copy batches on the copy stream          */

@@ -54,8 +54,9 @@ class moe_trace_rec_t(C.Structure):
 
 class moe_timing_t(C.Structure):
     _fields_ = [("ffn_launches", C.c_uint64), ("ffn_gate_up_ms", C.c_double), ("ffn_down_ms", C.c_double),
-                ("route_ms", C.c_double), ("copies", C.c_uint64), ("copy_bytes", C.c_uint64),
-                ("copy_ms", C.c_double)]
+                ("ffn_fused_launches", C.c_uint64), ("ffn_fused_ms", C.c_double),
+                ("route_launches", C.c_uint64), ("route_ms", C.c_double),
+                ("copies", C.c_uint64), ("copy_bytes", C.c_uint64), ("copy_ms", C.c_double)]
 
 
 class MoeError(RuntimeError):

@@ -21,7 +21,7 @@
 //
 // Tiled layout of one expert block (bf16 elements, total 3*d*f):
 //   [f/16 row tiles][d/32 k-blocks][gate,up][64 lanes][8]   then
-//   [d/16 row tiles][f/32 k-blocks][64 lanes][8]
+//   [f/32 k-blocks][d/16 row tiles][64 lanes][8]
 // with lane l, element j of a fragment holding W[row0 + l%16][k0 + (l/16)*8 + j].
 #include "device_utils.hpp"
 #include "moe_internal.hpp"
@@ -55,9 +55,17 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_tiled_kernel(FfnArgs a) {
   const int nkb = kdim >> 5;
   const int kb0 = (int)((long)wave * nkb / WAVES), kb1 = (int)((long)(wave + 1) * nkb / WAVES);
 
+  // fragment (tile, kb, m) of the gate/up section sits at ((tile*nkb + kb)*2 + m)*64 uint4;
+  // fragment (tile, kb) of the down section at (kb*(d/16) + tile)*64 behind it
   const uint4* w = reinterpret_cast<const uint4*>(group_weights(a, g));
-  if (NMAT == 1) w += (size_t)2 * a.f * a.d / 8;         // skip the gate/up section
-  w += (size_t)tile * nkb * NMAT * 64 + lane;
+  size_t kb_stride;
+  if (NMAT == 2) {
+    w += (size_t)tile * nkb * 2 * 64 + lane;
+    kb_stride = 2 * 64;
+  } else {
+    w += (size_t)2 * a.f * a.d / 8 + (size_t)tile * 64 + lane;
+    kb_stride = (size_t)(a.d >> 4) * 64;
+  }
 
   const int begin = a.t.grp_begin[g], cnt = a.t.grp_count[g];
 
@@ -89,7 +97,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_tiled_kernel(FfnArgs a) {
       for (int i = 0; i < CH; ++i)
 #pragma unroll
         for (int m = 0; m < NMAT; ++m)
-          wf[i][m] = (kb + i < kb1) ? w[((size_t)(kb + i) * NMAT + m) * 64] : uint4{0, 0, 0, 0};
+          wf[i][m] = (kb + i < kb1) ? w[(size_t)(kb + i) * kb_stride + m * 64] : uint4{0, 0, 0, 0};
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) {
         if (tok0 + tt * 16 < cnt) {   // uniform

@@ -48,6 +48,7 @@ struct ProfSlot {
   KernelEvents route, gate_up, down;   // attached to the dispatches of the three main kernels of a call
   bool used = false;
   bool mixed = false;  // the call also fetched experts: its resident-pass FFN covers only part of the K experts
+  bool fused = false;  // the call used the single-launch decode FFN (timed by `gate_up`)
 };
 struct CopySlot {
   hipEvent_t c0 = nullptr, c1 = nullptr;
@@ -229,16 +230,22 @@ int issue_copies(moe_cache* c, int layer, int n) {
 
 int drain_prof_slot(moe_cache* c, ProfSlot& p) {
   if (!p.used) return MOE_OK;
-  HIPCHK(hipEventSynchronize(p.down.stop));
+  HIPCHK(hipEventSynchronize(p.fused ? p.gate_up.stop : p.down.stop));
   float a = 0.f, b = 0.f, r = 0.f;
   HIPCHK(hipEventElapsedTime(&r, p.route.start, p.route.stop));
   HIPCHK(hipEventElapsedTime(&a, p.gate_up.start, p.gate_up.stop));
-  HIPCHK(hipEventElapsedTime(&b, p.down.start, p.down.stop));
+  if (!p.fused) HIPCHK(hipEventElapsedTime(&b, p.down.start, p.down.stop));
   c->timing.route_ms += r;
+  c->timing.route_launches += 1;
   if (!p.mixed) {
-    c->timing.ffn_gate_up_ms += a;
-    c->timing.ffn_down_ms += b;
-    c->timing.ffn_launches += 1;
+    if (p.fused) {
+      c->timing.ffn_fused_ms += a;
+      c->timing.ffn_fused_launches += 1;
+    } else {
+      c->timing.ffn_gate_up_ms += a;
+      c->timing.ffn_down_ms += b;
+      c->timing.ffn_launches += 1;
+    }
   }
   p.used = false;
   return MOE_OK;
@@ -275,11 +282,11 @@ int moe_pack_expert(const void* src_rowmajor, void* dst_tiled, int32_t d, int32_
         for (int l = 0; l < 64; ++l)
           memcpy(out + l * 8, w + (size_t)(ft * 16 + (l & 15)) * d + kb * 32 + (l >> 4) * 8, 16);
       }
-  // down section: [d/16][f/32][64][8]
+  // down section: [f/32][d/16][64][8]  (all row tiles of one 32-column block of W_d are contiguous)
   uint16_t* dsec = dst + (size_t)2 * f * d;
-  for (int dt = 0; dt < d / 16; ++dt)
-    for (int kb = 0; kb < nkb_f; ++kb) {
-      uint16_t* out = dsec + ((size_t)dt * nkb_f + kb) * 512;
+  for (int kb = 0; kb < nkb_f; ++kb)
+    for (int dt = 0; dt < d / 16; ++dt) {
+      uint16_t* out = dsec + ((size_t)kb * (d / 16) + dt) * 512;
       for (int l = 0; l < 64; ++l)
         memcpy(out + l * 8, wd + (size_t)(dt * 16 + (l & 15)) * f + kb * 32 + (l >> 4) * 8, 16);
     }
@@ -395,7 +402,13 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->t.n_groups = reinterpret_cast<int32_t*>(c->call_mem + o_ng);
   c->arrive = reinterpret_cast<int32_t*>(c->call_mem + o_arr);
   CREATE_CHK(hipMalloc(&c->h, NP * cfg->d_ff * 4), MOE_ERR_HIP);
-  CREATE_CHK(hipMalloc(reinterpret_cast<void**>(&c->o), NP * cfg->d_model * 4), MOE_ERR_HIP);
+  size_t o_bytes = NP * cfg->d_model * 4;
+  if (cfg->pool_layout == MOE_LAYOUT_TILED && ffn_fused_supported(cfg->d_model, cfg->d_ff, 1)) {
+    // the single-launch decode FFN keeps one partial sum per 32-row chunk of d_ff, for calls of up to 16 tokens
+    const size_t pairs = (size_t)std::min(Bm, 16) * KS;
+    o_bytes = std::max(o_bytes, pairs * (size_t)(cfg->d_ff / 32) * cfg->d_model * 4);
+  }
+  CREATE_CHK(hipMalloc(reinterpret_cast<void**>(&c->o), o_bytes), MOE_ERR_HIP);
 
   // ---- pinned mailbox ----
   const size_t hm = align_up(sizeof(Mailbox), 64) + align_up((size_t)C * 4, 64) + (size_t)c->max_miss * sizeof(MissEntry);
@@ -530,12 +543,15 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   fa.max_count = batch;
   fa.t = c->t; fa.h = c->h; fa.o = c->o;
   const bool tiled = cf.pool_layout == MOE_LAYOUT_TILED;
+  const bool fused = tiled && ffn_fused_supported(d, cf.d_ff, batch);
+  fa.fused = fused ? 1 : 0;
   const KernelEvents ke1 = ps ? ps->gate_up : KernelEvents{}, ke2 = ps ? ps->down : KernelEvents{};
 
   // Experts that were already resident: their FFN starts right behind the cache
   // lookups, before the host knows the miss list.
   fa.pass = 0;
-  HIPCHK(tiled ? launch_ffn_tiled(s, fa, ke1, ke2) : launch_ffn_rowmajor(s, cf.dtype, fa, ke1, ke2));
+  HIPCHK(fused ? launch_ffn_fused(s, fa, ke1)
+               : (tiled ? launch_ffn_tiled(s, fa, ke1, ke2) : launch_ffn_rowmajor(s, cf.dtype, fa, ke1, ke2)));
 
   HIPCHK(hipEventSynchronize(c->ev_mail));
   const uint32_t got = __atomic_load_n(&c->mailbox->seq, __ATOMIC_ACQUIRE);
@@ -550,11 +566,13 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
     HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0));
     c->copies_pending = false;
     fa.pass = 1;
-    HIPCHK(tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
-                 : launch_ffn_rowmajor(s, cf.dtype, fa, KernelEvents{}, KernelEvents{}));
+    HIPCHK(fused ? launch_ffn_fused(s, fa, KernelEvents{})
+                 : (tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
+                          : launch_ffn_rowmajor(s, cf.dtype, fa, KernelEvents{}, KernelEvents{})));
   }
-  if (ps) { ps->used = true; ps->mixed = mb.n_miss > 0; }
-  HIPCHK(launch_combine(s, cf.dtype, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, y_dev));
+  if (ps) { ps->used = true; ps->mixed = mb.n_miss > 0; ps->fused = fused; }
+  HIPCHK(fused ? launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev)
+               : launch_combine(s, cf.dtype, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, y_dev));
 
   moe_cache_stats_t& st = c->stats[layer];
   st.lookups += (uint64_t)batch * K;

@@ -76,7 +76,8 @@ struct FfnArgs {
   int32_t max_count;       // upper bound on tokens per group (= batch)
   CallTables t;
   void* h;                 // [B*KS][f]  fp32 (row-major path) or bf16 (tiled path)
-  float* o;                // [B*KS][d]
+  float* o;                // [B*KS][d]; fused path: partial sums [pairs][f/32][d]
+  int32_t fused;           // 1: o holds per-chunk partial sums (fused decode kernel)
   int32_t pass;            // 0: groups whose buffer was resident, 1: groups fetched by this call, 2: all
 };
 
@@ -107,6 +108,10 @@ hipError_t launch_pin(hipStream_t s, const LayerState& st, const CallTables& t, 
 hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace);
 hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
+bool ffn_fused_supported(int d, int f, int max_count);
+hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev);
+hipError_t launch_combine_chunks(hipStream_t s, const float* o_part, const float* wpair, const int32_t* pos_of,
+                                 int B, int KS, int d, int n_chunks, void* y);
 hipError_t launch_combine(hipStream_t s, int dtype, const float* o, const float* wpair, const int32_t* pos_of,
                           int B, int KS, int d, void* y);
 

@@ -115,7 +115,7 @@ def test_pack_expert_is_the_documented_permutation(B):
     B.moe_pack_expert(src, dst, d, f)
     wg, wu, wd = src[:f * d].reshape(f, d), src[f * d:2 * f * d].reshape(f, d), src[2 * f * d:].reshape(d, f)
     gu = dst[:2 * f * d].reshape(f // 16, d // 32, 2, 64, 8)
-    dn = dst[2 * f * d:].reshape(d // 16, f // 32, 64, 8)
+    dn = dst[2 * f * d:].reshape(f // 32, d // 16, 64, 8)
     lane = np.arange(64)
     for ft in range(f // 16):
         for kb in range(d // 32):
@@ -126,7 +126,7 @@ def test_pack_expert_is_the_documented_permutation(B):
     for dt in range(d // 16):
         for kb in range(f // 32):
             for j in range(8):
-                np.testing.assert_array_equal(dn[dt, kb, :, j], wd[dt * 16 + lane % 16, kb * 32 + (lane // 16) * 8 + j])
+                np.testing.assert_array_equal(dn[kb, dt, :, j], wd[dt * 16 + lane % 16, kb * 32 + (lane // 16) * 8 + j])
     assert sorted(dst.tolist()) == sorted(src.tolist())
     bad = np.zeros(3 * 48 * 64, dtype=np.uint16)
     assert B.lib.moe_pack_expert(bad.ctypes.data, bad.ctypes.data, 48, 64) == B.MOE_ERR_UNSUPPORTED

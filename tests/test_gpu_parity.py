@@ -106,6 +106,22 @@ def test_small_bf16_batched_with_evictions_inside_a_call(torch, P, tiled, batch)
     cache.close()
 
 
+@pytest.mark.parametrize("d_model,d_ff", [(256, 96), (512, 160), (1024, 64)])
+@pytest.mark.parametrize("batch", [1, 4, 16, 17])
+def test_single_launch_decode_ffn_shapes(torch, P, d_model, d_ff, batch):
+    # hidden widths that are multiples of 256 take the single-launch decode FFN for calls of up to 16 tokens;
+    # 17 tokens fall back to the two-kernel path on the same cache
+    cfg = small_cfg(d_model=d_model, d_ff=d_ff, n_seqs=17, n_steps=4, n_layers=1, capacity=16, n_shared=1)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=17, trace_capacity=4096)
+    ost = OracleStack(wl, capacity=16, keep=16)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, list(range(batch)), step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_lru_table_larger_than_a_wave(torch, P):
     # capacity above 64 slots: the cache table is staged in LDS instead of registers
     cfg = small_cfg(n_experts=96, capacity=70, n_layers=1, n_seqs=2, n_steps=40, pref_lo=0, pref_hi=0, beta=0.0)

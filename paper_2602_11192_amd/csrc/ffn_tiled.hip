@@ -33,6 +33,13 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// weights are read once per call: nontemporal, so that they do not displace the tokens, h and the router matrix
+__device__ __forceinline__ uint4 ldw(const uint4* p) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return uint4{v.x, v.y, v.z, v.w};
+}
+
 __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int g) {
   const int id = a.t.grp_buf[g];
   return id < a.P ? a.buffers + (size_t)id * a.expert_bytes
@@ -97,7 +104,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_tiled_kernel(FfnArgs a) {
       for (int i = 0; i < CH; ++i)
 #pragma unroll
         for (int m = 0; m < NMAT; ++m)
-          wf[i][m] = (kb + i < kb1) ? w[(size_t)(kb + i) * kb_stride + m * 64] : uint4{0, 0, 0, 0};
+          wf[i][m] = (kb + i < kb1) ? ldw(w + (size_t)(kb + i) * kb_stride + m * 64) : uint4{0, 0, 0, 0};
 #pragma unroll
       for (int tt = 0; tt < TT; ++tt) {
         if (tok0 + tt * 16 < cnt) {   // uniform

@@ -33,6 +33,8 @@ def parse():
     ap.add_argument("--workload", default="olmoe_like")
     ap.add_argument("--cpu-baseline-tokens", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run one plain 256 MiB copy kernel (reference dispatch for profiler memory counters)")
     return ap.parse_args()
 
 
@@ -147,6 +149,13 @@ def main():
     from workload import Workload, get_config
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
+
+    if a.calibrate_copy:
+        n = 256 << 20
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty(n, dtype=torch.uint8, device="cuda")
+        P.B.moe_probe_stream(src, dst, n, 1, 1)
+        del src, dst
 
     cfg = get_config(a.workload)
     wl = Workload(cfg)

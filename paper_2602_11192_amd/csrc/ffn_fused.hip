@@ -45,8 +45,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // call finds its matrix still cached).
 __device__ __forceinline__ u32x4 ldw(const u32x4* p) { return __builtin_nontemporal_load(p); }
 
-__device__ __forceinline__ const char* group_weights(const FfnArgs& a, int g) {
-  const int id = a.t.grp_buf[g];
+__device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
   return id < a.P ? a.buffers + (size_t)id * a.expert_bytes
                   : a.shared + (size_t)(id - a.P) * a.expert_bytes;
 }
@@ -57,8 +56,9 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
   __shared__ float red[WAVES][2][256];            // partial gate / up tiles of the waves
   __shared__ __align__(16) uint16_t hs[16][32];   // h of the chunk, bf16, [token][row in chunk]
   const int g = blockIdx.y;
-  if (g >= *a.t.n_groups) return;
-  if (a.pass != 2 && a.t.grp_miss[g] != a.pass) return;
+  const int ng = *a.t.n_groups;        // both loads are issued before the first branch: one round trip
+  const GroupDesc gd = a.t.grp[g];
+  if (g >= ng || (a.pass != 2 && gd.miss != a.pass)) return;
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -76,15 +76,15 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
   const int kb0 = ks, kb_step = KS;
 
   const size_t x_step = (size_t)kb_step * 32, w_step = (size_t)kb_step * 128;
-  const u32x4* wbase = reinterpret_cast<const u32x4*>(group_weights(a, g));
+  const u32x4* wbase = reinterpret_cast<const u32x4*>(group_weights(a, gd.buf));
   // gate/up fragment (row tile 2c+tile, kb, m) and W_d fragment (chunk c, row tile dt)
   const u32x4* wa = wbase + ((size_t)(2 * c + tile) * nkb_d + kb0) * 2 * 64 + lane;
   const u32x4* wb = wbase + (size_t)2 * a.f * d / 8 + ((size_t)c * n_dt + wave) * 64 + lane;
 
-  const int begin = a.t.grp_begin[g], cnt = a.t.grp_count[g];
+  const int begin = gd.begin, cnt = gd.count;
   const uint16_t* xrow = nullptr;
   if (n < cnt) {
-    const int p = a.t.sorted_pair[begin + n];
+    const int p = n == 0 ? gd.pair0 : a.t.sorted_pair[begin + n];   // a single-token group needs no second look-up
     xrow = reinterpret_cast<const uint16_t*>(a.x) + (size_t)(p / a.KS) * d + (size_t)kb0 * 32 + q * 8;
   }
 

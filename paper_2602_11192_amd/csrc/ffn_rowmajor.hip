@@ -11,28 +11,25 @@ namespace {
 
 constexpr int kRowsPerBlock = 4;
 
-__device__ __forceinline__ const char* group_weights(const FfnArgs& a, int g) {
-  const int id = a.t.grp_buf[g];
+__device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
   return id < a.P ? a.buffers + (size_t)id * a.expert_bytes
                   : a.shared + (size_t)(id - a.P) * a.expert_bytes;
-}
-
-__device__ __forceinline__ bool group_in_pass(const FfnArgs& a, int g) {
-  return a.pass == 2 || a.t.grp_miss[g] == a.pass;
 }
 
 // h[pos][j] = silu(W_g[j,:].x) * (W_u[j,:].x)
 template <typename T>
 __global__ void __launch_bounds__(64 * kRowsPerBlock) gate_up_rowmajor(FfnArgs a) {
   const int g = blockIdx.y;
-  if (g >= *a.t.n_groups || !group_in_pass(a, g)) return;
+  const int ng = *a.t.n_groups;
+  const GroupDesc gd = a.t.grp[g];
+  if (g >= ng || (a.pass != 2 && gd.miss != a.pass)) return;
   const int lane = threadIdx.x & 63;
   const int j = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (j >= a.f) return;
-  const T* w = reinterpret_cast<const T*>(group_weights(a, g));
+  const T* w = reinterpret_cast<const T*>(group_weights(a, gd.buf));
   const T* wg = w + (size_t)j * a.d;
   const T* wu = w + (size_t)a.f * a.d + (size_t)j * a.d;
-  const int begin = a.t.grp_begin[g], cnt = a.t.grp_count[g];
+  const int begin = gd.begin, cnt = gd.count;
   float* h = reinterpret_cast<float*>(a.h);
   for (int tkn = 0; tkn < cnt; ++tkn) {
     const int p = a.t.sorted_pair[begin + tkn];
@@ -53,12 +50,14 @@ __global__ void __launch_bounds__(64 * kRowsPerBlock) gate_up_rowmajor(FfnArgs a
 template <typename T>
 __global__ void __launch_bounds__(64 * kRowsPerBlock) down_rowmajor(FfnArgs a) {
   const int g = blockIdx.y;
-  if (g >= *a.t.n_groups || !group_in_pass(a, g)) return;
+  const int ng = *a.t.n_groups;
+  const GroupDesc gd = a.t.grp[g];
+  if (g >= ng || (a.pass != 2 && gd.miss != a.pass)) return;
   const int lane = threadIdx.x & 63;
   const int i = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
   if (i >= a.d) return;
-  const T* wd = reinterpret_cast<const T*>(group_weights(a, g)) + (size_t)2 * a.f * a.d + (size_t)i * a.f;
-  const int begin = a.t.grp_begin[g], cnt = a.t.grp_count[g];
+  const T* wd = reinterpret_cast<const T*>(group_weights(a, gd.buf)) + (size_t)2 * a.f * a.d + (size_t)i * a.f;
+  const int begin = gd.begin, cnt = gd.count;
   const float* h = reinterpret_cast<const float*>(a.h);
   for (int tkn = 0; tkn < cnt; ++tkn) {
     const float* hr = h + (size_t)(begin + tkn) * a.f;

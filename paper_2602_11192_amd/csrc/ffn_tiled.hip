@@ -40,8 +40,7 @@ __device__ __forceinline__ uint4 ldw(const uint4* p) {
   return uint4{v.x, v.y, v.z, v.w};
 }
 
-__device__ __forceinline__ const char* group_weights(const FfnArgs& a, int g) {
-  const int id = a.t.grp_buf[g];
+__device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
   return id < a.P ? a.buffers + (size_t)id * a.expert_bytes
                   : a.shared + (size_t)(id - a.P) * a.expert_bytes;
 }
@@ -50,8 +49,9 @@ template <int NMAT, int WAVES, int CH, int TT>
 __global__ void __launch_bounds__(64 * WAVES) ffn_tiled_kernel(FfnArgs a) {
   __shared__ float red[WAVES][TT][NMAT][256];
   const int g = blockIdx.y;
-  if (g >= *a.t.n_groups) return;
-  if (a.pass != 2 && a.t.grp_miss[g] != a.pass) return;
+  const int ng = *a.t.n_groups;        // both loads are issued before the first branch: one round trip
+  const GroupDesc gd = a.t.grp[g];
+  if (g >= ng || (a.pass != 2 && gd.miss != a.pass)) return;
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -64,7 +64,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_tiled_kernel(FfnArgs a) {
 
   // fragment (tile, kb, m) of the gate/up section sits at ((tile*nkb + kb)*2 + m)*64 uint4;
   // fragment (tile, kb) of the down section at (kb*(d/16) + tile)*64 behind it
-  const uint4* w = reinterpret_cast<const uint4*>(group_weights(a, g));
+  const uint4* w = reinterpret_cast<const uint4*>(group_weights(a, gd.buf));
   size_t kb_stride;
   if (NMAT == 2) {
     w += (size_t)tile * nkb * 2 * 64 + lane;
@@ -74,7 +74,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_tiled_kernel(FfnArgs a) {
     kb_stride = (size_t)(a.d >> 4) * 64;
   }
 
-  const int begin = a.t.grp_begin[g], cnt = a.t.grp_count[g];
+  const int begin = gd.begin, cnt = gd.count;
 
   for (int tok0 = 0; tok0 < cnt; tok0 += 16 * TT) {
     const uint16_t* brow[TT];

@@ -382,10 +382,8 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   const size_t o_pb = cm; cm += align_up(NP * 4, 16);
   const size_t o_sp = cm; cm += align_up(NP * 4, 16);
   const size_t o_po = cm; cm += align_up(NP * 4, 16);
-  const size_t o_gb = cm; cm += align_up((size_t)c->G * 4, 16);
-  const size_t o_gbeg = cm; cm += align_up((size_t)c->G * 4, 16);
-  const size_t o_gc = cm; cm += align_up((size_t)c->G * 4, 16);
-  const size_t o_gm = cm; cm += align_up((size_t)c->G * 4, 16);
+  cm = align_up(cm, 32);
+  const size_t o_gd = cm; cm += (size_t)c->G * sizeof(GroupDesc);
   const size_t o_ng = cm; cm += 16;
   const size_t o_arr = cm; cm += 16;
   CREATE_CHK(hipMalloc(&c->call_mem, cm), MOE_ERR_HIP);
@@ -395,10 +393,7 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->t.pair_buf = reinterpret_cast<int32_t*>(c->call_mem + o_pb);
   c->t.sorted_pair = reinterpret_cast<int32_t*>(c->call_mem + o_sp);
   c->t.pos_of = reinterpret_cast<int32_t*>(c->call_mem + o_po);
-  c->t.grp_buf = reinterpret_cast<int32_t*>(c->call_mem + o_gb);
-  c->t.grp_begin = reinterpret_cast<int32_t*>(c->call_mem + o_gbeg);
-  c->t.grp_count = reinterpret_cast<int32_t*>(c->call_mem + o_gc);
-  c->t.grp_miss = reinterpret_cast<int32_t*>(c->call_mem + o_gm);
+  c->t.grp = reinterpret_cast<GroupDesc*>(c->call_mem + o_gd);
   c->t.n_groups = reinterpret_cast<int32_t*>(c->call_mem + o_ng);
   c->arrive = reinterpret_cast<int32_t*>(c->call_mem + o_arr);
   CREATE_CHK(hipMalloc(&c->h, NP * cfg->d_ff * 4), MOE_ERR_HIP);

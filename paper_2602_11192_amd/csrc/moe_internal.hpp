@@ -39,6 +39,17 @@ struct Mailbox {
   int32_t pad[2];
 };
 
+// One group = the (token, expert) pairs of a call that read the same expert buffer.  A single 32-byte record so
+// that an FFN workgroup learns everything it needs to start streaming weights in one memory round trip.
+struct __attribute__((aligned(32))) GroupDesc {
+  int32_t buf;     // buffer id (>= P: shared expert P + s)
+  int32_t begin;   // first position of the group in sorted_pair
+  int32_t count;   // pairs in the group
+  int32_t miss;    // 1 if the buffer is being filled by this call
+  int32_t pair0;   // sorted_pair[begin], the group's first pair (its token is pair0 / KS)
+  int32_t pad[3];
+};
+
 // Per-call scratch tables (device).
 struct CallTables {
   int32_t* idx;          // [B][K]  selected experts, ascending id
@@ -46,10 +57,7 @@ struct CallTables {
   int32_t* pair_buf;     // [B*KS]  buffer id the pair reads (>= P: shared expert P + s)
   int32_t* sorted_pair;  // [B*KS]  pairs ordered by buffer id, stable
   int32_t* pos_of;       // [B*KS]  inverse of sorted_pair
-  int32_t* grp_buf;      // [G]
-  int32_t* grp_begin;    // [G]
-  int32_t* grp_count;    // [G]
-  int32_t* grp_miss;     // [G]     1 if the buffer is being filled by this call
+  GroupDesc* grp;        // [G]     one record per distinct expert buffer of the call
   int32_t* n_groups;     // [1]     number of groups of the call (0 if the call failed)
 };
 

@@ -364,10 +364,10 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
       for (int id = 0; id < NB; ++id) {
         const int c = count[id];
         if (c > 0) {
-          t.grp_buf[n_groups] = id;
-          t.grp_begin[n_groups] = off;
-          t.grp_count[n_groups] = c;
-          t.grp_miss[n_groups] = id < P ? filled[id] : 0;
+          t.grp[n_groups].buf = id;
+          t.grp[n_groups].begin = off;
+          t.grp[n_groups].count = c;
+          t.grp[n_groups].miss = id < P ? filled[id] : 0;
           ++n_groups;
         }
         start[id] = off;
@@ -380,6 +380,8 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
       }
     }
     n_groups = __shfl(n_groups, 0);
+    wave_sync();
+    for (int gi = lane; gi < n_groups; gi += kWave) t.grp[gi].pair0 = t.sorted_pair[t.grp[gi].begin];
   }
   if (a.mode == 0 && lane == 0) *t.n_groups = n_groups;
   PHASE_TS(6);
@@ -561,10 +563,11 @@ __device__ void cache_phase_fast(FastTable f, int my_e, const LayerState& st, co
       t.sorted_pair[rank] = lane;
       t.pos_of[lane] = rank;
       if (is_first) {
-        t.grp_buf[gidx] = my_pair;
-        t.grp_begin[gidx] = rank;
-        t.grp_count[gidx] = cnt;
-        t.grp_miss[gidx] = my_pair < P ? was_filled : 0;
+        GroupDesc gd;
+        gd.buf = my_pair; gd.begin = rank; gd.count = cnt; gd.miss = my_pair < P ? was_filled : 0;
+        gd.pair0 = lane;      // stable order: the group's first pair is its lowest pair id
+        gd.pad[0] = gd.pad[1] = gd.pad[2] = 0;
+        t.grp[gidx] = gd;
       }
     }
     n_groups = __popcll(fm);

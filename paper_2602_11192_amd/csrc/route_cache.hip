@@ -77,6 +77,12 @@ __device__ __forceinline__ void wave_sync() {
 
 __device__ __forceinline__ int readlane_i(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
 
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // ---------------------------------------------------------------- LDS layout
 struct LdsLayout {
   size_t tick, score, expert_in, buf_of_slot, slot_of, free_buf, zombie, used, filled, pending, count, start,
@@ -85,8 +91,9 @@ struct LdsLayout {
 
 __host__ __device__ inline bool stage_in_lds(int B, int KS) { return (size_t)B * KS <= kStageMaxPairs; }
 
-__host__ __device__ inline bool fast_table(int policy, int C, int P, int n_pairs) {
-  return policy == MOE_POLICY_LRU && C <= kWave && P <= kWave && n_pairs <= kWave;
+// The register-resident table: LRU, at most 64 slots and 64 buffers, and at most 128 buffer ids in all.
+__host__ __device__ inline bool fast_table(int policy, int C, int P, int n_shared) {
+  return policy == MOE_POLICY_LRU && C <= kWave && P <= kWave && P + n_shared <= 2 * kWave;
 }
 
 __host__ __device__ inline LdsLayout lds_layout(int E, int C, int P, int n_shared, int B, int K, int KS) {
@@ -199,6 +206,58 @@ __device__ __forceinline__ void gate_token(const float* zs, int b, int E, int K,
     base += __popcll(m);
   }
   if (lane < KS - K) wpair_g[(size_t)b * KS + K + lane] = 1.0f;  // shared experts: weight 1
+}
+
+// ---------------------------------------------------------------- grouping (any number of pairs)
+// Counting sort of the (token, expert) pairs by the buffer they read, run by ONE wave with counters in LDS.
+// pair_buf[B*KS] must hold the buffer of every routed pair; shared-expert pairs are filled in here.
+// The order of the pairs inside a group is whatever order the LDS atomics resolve in; every pair's arithmetic is
+// independent of its position, so the layer output does not depend on it.
+__device__ int group_pairs_lds(int32_t* count, int32_t* cursor, const int32_t* filled, int32_t* pair_buf,
+                               const CallTables& t, const CacheCallArgs& a) {
+  const int lane = threadIdx.x & 63;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const int K = a.K, KS = a.KS, P = a.P;
+  const int NP = a.B * KS, NB = P + a.n_shared;
+  for (int p = lane; p < a.B * a.n_shared; p += kWave) {
+    const int b = p / a.n_shared, sidx = p - b * a.n_shared;
+    pair_buf[(size_t)b * KS + K + sidx] = P + sidx;
+  }
+  for (int i = lane; i < NB; i += kWave) count[i] = 0;
+  wave_sync();
+  for (int p = lane; p < NP; p += kWave) atomicAdd(&count[pair_buf[p]], 1);
+  wave_sync();
+  int n_groups = 0, offset = 0;
+  for (int base = 0; base < NB; base += kWave) {        // ids in ascending order, 64 at a time
+    const int id = base + lane;
+    const int c = id < NB ? count[id] : 0;
+    int incl = c;                                       // inclusive prefix sum over the lanes
+#pragma unroll
+    for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+      const int v = __shfl_up(incl, dlt);
+      if (lane >= dlt) incl += v;
+    }
+    const int begin = offset + incl - c;
+    const uint64_t gm = __ballot(c > 0);
+    if (c > 0) {
+      GroupDesc gd;
+      gd.buf = id; gd.begin = begin; gd.count = c; gd.miss = id < P ? filled[id] : 0;
+      gd.pair0 = 0; gd.pad[0] = gd.pad[1] = gd.pad[2] = 0;
+      t.grp[n_groups + __popcll(gm & lt_mask)] = gd;
+    }
+    if (id < NB) cursor[id] = begin;
+    n_groups += __popcll(gm);
+    offset += __shfl(incl, kWave - 1);
+  }
+  wave_sync();
+  for (int p = lane; p < NP; p += kWave) {
+    const int pos = atomicAdd(&cursor[pair_buf[p]], 1);
+    t.sorted_pair[pos] = p;
+    t.pos_of[p] = pos;
+  }
+  wave_sync();
+  for (int gi = lane; gi < n_groups; gi += kWave) t.grp[gi].pair0 = t.sorted_pair[t.grp[gi].begin];
+  return n_groups;
 }
 
 // ---------------------------------------------------------------- phase 3
@@ -348,40 +407,7 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
   PHASE_TS(5);
   int n_groups = 0;
   if (status == MOE_OK && a.mode == 0) {
-    // ---- group the (token, expert) pairs by the buffer they read: stable counting sort ----
-    const int NP = a.B * KS;
-    const int NB = P + a.n_shared;
-    for (int p = lane; p < a.B * a.n_shared; p += kWave) {
-      const int b = p / a.n_shared, sidx = p % a.n_shared;
-      pair_buf[(size_t)b * KS + K + sidx] = P + sidx;
-    }
-    for (int i = lane; i < NB; i += kWave) count[i] = 0;
-    wave_sync();
-    for (int p = lane; p < NP; p += kWave) atomicAdd(&count[pair_buf[p]], 1);
-    wave_sync();
-    if (lane == 0) {
-      int off = 0;
-      for (int id = 0; id < NB; ++id) {
-        const int c = count[id];
-        if (c > 0) {
-          t.grp[n_groups].buf = id;
-          t.grp[n_groups].begin = off;
-          t.grp[n_groups].count = c;
-          t.grp[n_groups].miss = id < P ? filled[id] : 0;
-          ++n_groups;
-        }
-        start[id] = off;
-        off += c;
-      }
-      for (int p = 0; p < NP; ++p) {
-        const int pos = start[pair_buf[p]]++;
-        t.sorted_pair[pos] = p;
-        t.pos_of[p] = pos;
-      }
-    }
-    n_groups = __shfl(n_groups, 0);
-    wave_sync();
-    for (int gi = lane; gi < n_groups; gi += kWave) t.grp[gi].pair0 = t.sorted_pair[t.grp[gi].begin];
+    n_groups = group_pairs_lds(count, start, filled, pair_buf, t, a);
   }
   if (a.mode == 0 && lane == 0) *t.n_groups = n_groups;
   PHASE_TS(6);
@@ -434,11 +460,13 @@ struct FastTable {
 __device__ __forceinline__ FastTable fast_load(const LayerState& st, int C, int P) {
   const int lane = threadIdx.x & 63;
   FastTable f;
-  f.clock = st.scalars[SC_CLOCK];
-  f.n_res = (int)st.scalars[SC_NRES];
-  f.n_free = (int)st.scalars[SC_NFREE];
-  f.n_zombie = (int)st.scalars[SC_NZOMBIE];
-  f.trace_n = st.scalars[SC_TRACE_N];
+  // the scalars are the same in every lane; telling the compiler so keeps the loops over them and the
+  // cross-lane reads indexed by them on the scalar unit
+  f.clock = uniform64(st.scalars[SC_CLOCK]);
+  f.n_res = __builtin_amdgcn_readfirstlane((int)st.scalars[SC_NRES]);
+  f.n_free = __builtin_amdgcn_readfirstlane((int)st.scalars[SC_NFREE]);
+  f.n_zombie = __builtin_amdgcn_readfirstlane((int)st.scalars[SC_NZOMBIE]);
+  f.trace_n = uniform64(st.scalars[SC_TRACE_N]);
   f.exp = lane < C ? st.expert_in[lane] : -2;
   f.tick = lane < C ? st.tick[lane] : ~0ull;
   f.buf = lane < C ? st.buf_of_slot[lane] : -1;
@@ -471,12 +499,20 @@ __device__ __forceinline__ int wave_argmin_tick(uint64_t tick) {
   return __ffsll((unsigned long long)__ballot(tick == best)) - 1;
 }
 
-// Runs in ONE wave.  my_e: lane q < n_lookups holds the expert of lookup q (decode:
-// q = b*K + k; pin: q = list position).
-__device__ void cache_phase_fast(FastTable f, int my_e, const LayerState& st, const CallTables& t,
+// Runs in ONE wave.  idx_src: the experts to look up, in order (decode: [B][K]; pin: the list);
+// pair_buf: scratch [B*KS] (LDS or global), used when the call has more than 64 pairs.
+__device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayout& L, const int32_t* idx_src,
+                                 int32_t* pair_buf, const LayerState& st, const CallTables& t,
                                  const CacheCallArgs& a) {
   const int lane = threadIdx.x & 63;
   const int C = a.C, P = a.P, K = a.K, KS = a.KS;
+  // LDS scratch (the table itself lives in registers on this path)
+  int32_t* lds_slot_of = reinterpret_cast<int32_t*>(smem + L.slot_of);     // [E] expert -> slot
+  int32_t* lds_last = reinterpret_cast<int32_t*>(smem + L.free_buf);       // [P >= C] last lookup of a slot, +1
+  int32_t* lds_touch = reinterpret_cast<int32_t*>(smem + L.zombie);        // [P] buffer read by the chunk
+  int32_t* lds_filled = reinterpret_cast<int32_t*>(smem + L.filled);       // [P]
+  int32_t* lds_count = reinterpret_cast<int32_t*>(smem + L.count);         // [P + n_shared]
+  int32_t* lds_cursor = reinterpret_cast<int32_t*>(smem + L.start);        // [P + n_shared]
   // buffers released by the previous call: all its kernels have finished, reuse them
   {
     const int src = lane - f.n_free;
@@ -487,90 +523,141 @@ __device__ void cache_phase_fast(FastTable f, int my_e, const LayerState& st, co
   }
   const uint32_t seq = a.seq;
   const int n_lookups = a.mode == 0 ? a.B * K : K;
+  const int NP = a.B * KS;
+  const bool small = NP <= kWave;     // all pairs fit one per lane
   int status = MOE_OK, n_miss = 0, n_evict = 0, n_hits = 0;
-  int my_pair = -1;       // lane p = b*KS + k: buffer the pair reads
+  int my_pair = -1;       // small calls: lane p = b*KS + k holds the buffer the pair reads
   bool filled = false;    // lane p: buffer p is being filled by this call
   PHASE_TS(4);
 
-  for (int q = 0; q < n_lookups; ++q) {
-    const int e = readlane_i(my_e, q);
-    const uint64_t hm = __ballot(f.exp == e);
-    int s, buf, evicted = -1;
-    const bool hit = hm != 0;
-    if (hit) {
-      s = __ffsll((unsigned long long)hm) - 1;
-      buf = readlane_i(f.buf, s);
-      ++n_hits;
-    } else {
-      if (f.n_res < C) {          // slots fill in index order, so the lowest empty slot is n_res
-        s = f.n_res++;
-        buf = readlane_i(f.free_b, --f.n_free);
-      } else {
-        s = wave_argmin_tick(f.tick);
-        evicted = readlane_i(f.exp, s);
-        const int vb = readlane_i(f.buf, s);
-        if ((uint32_t)readlane_i((int)f.used, vb) == seq) {   // an earlier token of this call reads it
-          if (f.n_free == 0) { status = MOE_ERR_STAGING_EXHAUSTED; break; }
-          buf = readlane_i(f.free_b, --f.n_free);
-          if (lane == f.n_zombie) f.zomb = vb;
-          ++f.n_zombie;
-        } else {
-          buf = vb;
+  for (int chunk0 = 0; chunk0 < n_lookups && status == MOE_OK; chunk0 += kWave) {
+    const int nl = min(kWave, n_lookups - chunk0);
+    const int my_e = lane < nl ? idx_src[chunk0 + lane] : -3;
+    int my_buf = -1;      // lane q: buffer that lookup chunk0 + q reads
+    bool done = false;
+    if (a.mode == 0 && f.n_res > 0 && nl >= 16) {     // for a handful of lookups the in-order loop is cheaper
+      // ---- shortcut: if every lookup of the chunk hits, residency does not change inside the chunk and
+      //      the recency updates commute: the last lookup of a slot decides its tick ----
+      for (int e = lane; e < a.E; e += kWave) lds_slot_of[e] = -1;
+      if (lane < P) { lds_last[lane] = 0; lds_touch[lane] = 0; }
+      wave_sync();
+      if (lane < C && f.exp >= 0) lds_slot_of[f.exp] = lane;
+      wave_sync();
+      const int my_slot = lane < nl ? lds_slot_of[my_e] : -1;
+      if (__ballot(lane < nl && my_slot < 0) == 0) {
+        if (lane < nl) atomicMax(&lds_last[my_slot], lane + 1);
+        wave_sync();
+        const int last = lane < C ? lds_last[lane] : 0;
+        if (last > 0) {
+          f.tick = (uint64_t)(f.clock + last);
+          lds_touch[f.buf] = 1;
         }
-        ++n_evict;
+        wave_sync();
+        if (lane < P && lds_touch[lane]) f.used = seq;
+        my_buf = __shfl(f.buf, my_slot < 0 ? 0 : my_slot);
+        if (lane < nl && f.trace_n + chunk0 + lane < a.trace_cap)
+          st.trace[f.trace_n + chunk0 + lane] = moe_trace_rec_t{(chunk0 + lane) / K, my_e, 1, -1};
+        f.clock += nl;
+        n_hits += nl;
+        done = true;
       }
-      if (lane == s) { f.exp = e; f.buf = buf; }
-      if (lane == buf) filled = true;
-      if (lane == 0 && n_miss < a.max_miss) a.miss_list[n_miss] = MissEntry{e, buf};
-      ++n_miss;
     }
-    ++f.clock;
-    if (lane == s) f.tick = (uint64_t)f.clock;
-    if (lane == buf) f.used = seq;
-    if (a.mode == 0) {
-      const int b = q / K, k = q - b * K;
-      if (lane == b * KS + k) my_pair = buf;
-      if (lane == 0 && f.trace_n + q < a.trace_cap)
-        st.trace[f.trace_n + q] = moe_trace_rec_t{b, e, hit ? 1 : 0, evicted};
+    if (!done) {
+      for (int q = 0; q < nl; ++q) {
+        const int e = readlane_i(my_e, q);
+        const uint64_t hm = __ballot(f.exp == e);
+        int s, buf, evicted = -1;
+        const bool hit = hm != 0;
+        if (hit) {
+          s = __ffsll((unsigned long long)hm) - 1;
+          buf = readlane_i(f.buf, s);
+          ++n_hits;
+        } else {
+          if (f.n_res < C) {          // slots fill in index order, so the lowest empty slot is n_res
+            s = f.n_res++;
+            buf = readlane_i(f.free_b, --f.n_free);
+          } else {
+            s = wave_argmin_tick(f.tick);
+            evicted = readlane_i(f.exp, s);
+            const int vb = readlane_i(f.buf, s);
+            if ((uint32_t)readlane_i((int)f.used, vb) == seq) {   // an earlier token of this call reads it
+              if (f.n_free == 0) { status = MOE_ERR_STAGING_EXHAUSTED; break; }
+              buf = readlane_i(f.free_b, --f.n_free);
+              if (lane == f.n_zombie) f.zomb = vb;
+              ++f.n_zombie;
+            } else {
+              buf = vb;
+            }
+            ++n_evict;
+          }
+          if (lane == s) { f.exp = e; f.buf = buf; }
+          if (lane == buf) filled = true;
+          if (lane == 0 && n_miss < a.max_miss) a.miss_list[n_miss] = MissEntry{e, buf};
+          ++n_miss;
+        }
+        ++f.clock;
+        if (lane == s) f.tick = (uint64_t)f.clock;
+        if (lane == buf) f.used = seq;
+        if (lane == q) my_buf = buf;
+        if (a.mode == 0 && lane == 0 && f.trace_n + chunk0 + q < a.trace_cap)
+          st.trace[f.trace_n + chunk0 + q] = moe_trace_rec_t{(chunk0 + q) / K, e, hit ? 1 : 0, evicted};
+      }
+    }
+    if (a.mode == 0 && status == MOE_OK) {
+      if (small) {
+        // lane p = b*KS + k takes the buffer of lookup b*K + k (a single chunk)
+        const int b = lane / KS, k = lane - b * KS;
+        const int v = __shfl(my_buf, k < K ? b * K + k : 0);
+        if (lane < NP && k < K) my_pair = v;
+      } else if (lane < nl) {
+        const int l = chunk0 + lane, b = l / K;
+        pair_buf[(size_t)b * KS + (l - b * K)] = my_buf;
+      }
     }
   }
   PHASE_TS(5);
 
   int n_groups = 0;
   if (status == MOE_OK && a.mode == 0) {
-    // ---- group the pairs by buffer: rank every pair against all others (stable) ----
-    const int NP = a.B * KS;
-    {
-      const int b = lane / KS, k = lane - b * KS;
-      if (lane < NP && k >= K) my_pair = P + (k - K);     // shared experts
-    }
-    int rank = 0, same_before = 0, cnt = 0;
-    for (int q = 0; q < NP; ++q) {
-      const int bq = readlane_i(my_pair, q);
-      rank += (bq < my_pair || (bq == my_pair && q < lane)) ? 1 : 0;
-      cnt += bq == my_pair ? 1 : 0;
-      same_before += (bq == my_pair && q < lane) ? 1 : 0;
-    }
-    const bool is_first = lane < NP && same_before == 0;
-    const uint64_t fm = __ballot(is_first);
-    int gidx = 0;
-    for (uint64_t m = fm; m != 0; m &= m - 1) {
-      const int q = __ffsll((unsigned long long)m) - 1;
-      gidx += readlane_i(my_pair, q) < my_pair ? 1 : 0;
-    }
-    const int was_filled = __shfl((int)filled, my_pair < P && my_pair >= 0 ? my_pair : 0);
-    if (lane < NP) {
-      t.sorted_pair[rank] = lane;
-      t.pos_of[lane] = rank;
-      if (is_first) {
-        GroupDesc gd;
-        gd.buf = my_pair; gd.begin = rank; gd.count = cnt; gd.miss = my_pair < P ? was_filled : 0;
-        gd.pair0 = lane;      // stable order: the group's first pair is its lowest pair id
-        gd.pad[0] = gd.pad[1] = gd.pad[2] = 0;
-        t.grp[gidx] = gd;
+    if (small) {
+      // ---- group the pairs by buffer: rank every pair against all others (stable) ----
+      {
+        const int b = lane / KS, k = lane - b * KS;
+        if (lane < NP && k >= K) my_pair = P + (k - K);     // shared experts
       }
+      int rank = 0, same_before = 0, cnt = 0;
+      for (int q = 0; q < NP; ++q) {
+        const int bq = readlane_i(my_pair, q);
+        rank += (bq < my_pair || (bq == my_pair && q < lane)) ? 1 : 0;
+        cnt += bq == my_pair ? 1 : 0;
+        same_before += (bq == my_pair && q < lane) ? 1 : 0;
+      }
+      const bool is_first = lane < NP && same_before == 0;
+      const uint64_t fm = __ballot(is_first);
+      int gidx = 0;
+      for (uint64_t m = fm; m != 0; m &= m - 1) {
+        const int q = __ffsll((unsigned long long)m) - 1;
+        gidx += readlane_i(my_pair, q) < my_pair ? 1 : 0;
+      }
+      const int was_filled = __shfl((int)filled, my_pair < P && my_pair >= 0 ? my_pair : 0);
+      if (lane < NP) {
+        t.sorted_pair[rank] = lane;
+        t.pos_of[lane] = rank;
+        if (is_first) {
+          GroupDesc gd;
+          gd.buf = my_pair; gd.begin = rank; gd.count = cnt; gd.miss = my_pair < P ? was_filled : 0;
+          gd.pair0 = lane;      // stable order: the group's first pair is its lowest pair id
+          gd.pad[0] = gd.pad[1] = gd.pad[2] = 0;
+          t.grp[gidx] = gd;
+        }
+      }
+      n_groups = __popcll(fm);
+    } else {
+      // ---- more than 64 pairs: counting sort with the counters in LDS ----
+      if (lane < P) lds_filled[lane] = filled ? 1 : 0;
+      wave_sync();
+      n_groups = group_pairs_lds(lds_count, lds_cursor, lds_filled, pair_buf, t, a);
     }
-    n_groups = __popcll(fm);
   }
   if (a.mode == 0 && lane == 0) *t.n_groups = n_groups;
   PHASE_TS(6);
@@ -612,7 +699,7 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
   const int b = blockIdx.x;
   const int E = a.E, K = a.K, KS = a.KS, d = r.d;
   const bool single = gridDim.x == 1;
-  const bool fast = fast_table(a.policy, a.C, a.P, a.B * KS);
+  const bool fast = fast_table(a.policy, a.C, a.P, a.n_shared);
   PHASE_TS(0);
 
   // With one workgroup the cache table can be fetched while the router GEMV runs.
@@ -698,9 +785,7 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
 
   // ---- phase 3: cache lookups, one wave ----
   if (fast) {
-    const int n_lookups = a.B * K;
-    const int my_e = lane < n_lookups ? idx_stage[lane] : -1;
-    cache_phase_fast(ft, my_e, st, t, a);
+    cache_phase_fast(ft, smem, L, stage ? idx_stage : t.idx, pair_stage, st, t, a);
   } else {
     cache_phase_general(smem, L, stage ? idx_stage : t.idx, pair_stage, st, t, a);
   }
@@ -708,10 +793,9 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
 
 __global__ void __launch_bounds__(64) pin_kernel(LayerState st, CallTables t, CacheCallArgs a) {
   extern __shared__ __align__(8) unsigned char smem[];
-  const int lane = threadIdx.x;
-  if (fast_table(a.policy, a.C, a.P, a.K)) {
-    const int my_e = lane < a.K ? a.pin_ids[lane] : -1;
-    cache_phase_fast(fast_load(st, a.C, a.P), my_e, st, t, a);
+  if (fast_table(a.policy, a.C, a.P, a.n_shared)) {
+    const LdsLayout L = lds_layout(a.E, a.C, a.P, a.n_shared, 1, a.K, a.KS);
+    cache_phase_fast(fast_load(st, a.C, a.P), smem, L, a.pin_ids, nullptr, st, t, a);
   } else {
     const LdsLayout L = lds_layout(a.E, a.C, a.P, a.n_shared, 1, a.K, a.KS);
     cache_phase_general(smem, L, nullptr, nullptr, st, t, a);

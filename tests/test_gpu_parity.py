@@ -148,6 +148,38 @@ def test_alternating_small_and_large_batches_share_one_table(torch, P):
     cache.close()
 
 
+@pytest.mark.parametrize("gamma", [1.0, 0.7])
+def test_gamma_policy_batched(torch, P, gamma):
+    # batched calls under the discounted-count policy (table staged in LDS, general grouping)
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(n_seqs=20, n_steps=6, n_layers=1, capacity=7, n_shared=1)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=20, staging_buffers=20 * cfg.top_k, trace_capacity=8192,
+                         policy=B.MOE_POLICY_GAMMA, gamma=gamma)
+    ost = OracleStack(wl, policy=oracle.POLICY_GAMMA, gamma=gamma)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        rows = list(range(20)) if step % 2 == 0 else list(range(3, 9))
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, rows, step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+def test_resident_batch_with_64_buffers_and_shared_experts(torch, P):
+    # 64 expert buffers plus shared experts: buffer ids run past 64; 40 tokens = 240 pairs in one call
+    cfg = small_cfg(n_experts=64, capacity=64, top_k=4, n_shared=2, n_seqs=40, n_steps=3, n_layers=1,
+                    d_model=256, d_ff=64)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=40, trace_capacity=4096)
+    ost = OracleStack(wl, capacity=64, keep=64)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        rows = list(range(40)) if step != 1 else list(range(11))
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, rows, step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_staging_exhausted_leaves_cache_unchanged(torch, P):
     from paper_2602_11192_amd import binding as B
     cfg = small_cfg(n_seqs=8, n_steps=4, n_layers=1, capacity=4, pref_lo=0, pref_hi=0, beta=0.0)

@@ -1,0 +1,189 @@
+// Expert SwiGLU FFN (paper section 2, Eq. 3) as a grouped bf16 GEMM for calls
+// in which an expert sees many tokens (batched decode, prompt processing).
+//
+// One workgroup = 4 waves = a block of 64 output rows (4 MFMA row tiles, one
+// per wave) of one expert x a tile of up to 128 of that expert's tokens.
+//   * weights: A operand of v_mfma_f32_16x16x32_bf16, read by each wave straight
+//     from global memory in the tiled layout (one coalesced KiB per fragment,
+//     nontemporal: each fragment is used by exactly one wave of one token tile);
+//   * tokens: B operand, shared by the four waves, staged through LDS in
+//     fragment order (conflict-free 16-byte reads), double buffered two k-blocks
+//     at a time so that the loads of stage s+1 overlap the MFMAs of stage s;
+//   * accumulators: 8 column blocks x (gate, up) x 4 registers per lane.
+// Column blocks beyond the expert's token count are skipped, so a large batch
+// spread thinly over many experts degrades into weight streaming rather than
+// wasted matrix work.  NMAT = 2 computes h = silu(X W_g^T) * (X W_u^T) (bf16,
+// rows in group order); NMAT = 1 computes o = h W_d^T (fp32).
+#include "device_utils.hpp"
+#include "moe_internal.hpp"
+
+namespace moe {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kGemmWaves = 4;     // row tiles per workgroup
+constexpr int kTokTile = 128;     // tokens per workgroup
+constexpr int kColBlocks = kTokTile / 16;
+constexpr int kStageKb = 2;       // k-blocks (of 32) staged per step
+
+__device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
+  return id < a.P ? a.buffers + (size_t)id * a.expert_bytes
+                  : a.shared + (size_t)(id - a.P) * a.expert_bytes;
+}
+
+template <int NMAT>
+__global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
+  // [buffer][k-block in stage][column block][lane] x 16 bytes
+  __shared__ u32x4 xs[2][kStageKb][kColBlocks][64];
+  const int g = blockIdx.y;
+  const int ng = *a.t.n_groups;
+  const GroupDesc gd = a.t.grp[g];
+  if (g >= ng || (a.pass != 2 && gd.miss != a.pass)) return;
+  const int tok0 = blockIdx.z * kTokTile;
+  const int cnt = gd.count;
+  if (tok0 >= cnt) return;
+  const int n_tok = min(kTokTile, cnt - tok0);       // tokens of this tile
+  const int n_cb = (n_tok + 15) >> 4;                // column blocks in use
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int kdim = NMAT == 2 ? a.d : a.f;
+  const int nkb = kdim >> 5;
+  const int n_rt = (NMAT == 2 ? a.f : a.d) >> 4;
+  const int rt = blockIdx.x * kGemmWaves + wave;     // this wave's row tile
+  const bool has_rows = rt < n_rt;
+  const int rtc = has_rows ? rt : n_rt - 1;          // clamped: loads stay in bounds, results are dropped
+
+  const u32x4* w = reinterpret_cast<const u32x4*>(group_weights(a, gd.buf));
+  size_t kb_stride;
+  if (NMAT == 2) {
+    w += (size_t)rtc * nkb * 2 * 64 + lane;
+    kb_stride = 2 * 64;
+  } else {
+    w += (size_t)2 * a.f * a.d / 8 + (size_t)rtc * 64 + lane;
+    kb_stride = (size_t)(a.d >> 4) * 64;
+  }
+
+  // ---- staging assignment: 256 threads x 4 pieces of 16 bytes = 128 rows x 128 bytes (2 k-blocks) ----
+  const uint16_t* src[4];
+  int dst[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int idx = threadIdx.x + 256 * i;
+    const int r = idx >> 3, sg = idx & 7;              // token row of the tile, 16-byte segment of its 128 bytes
+    const int kbl = sg >> 2, q = sg & 3;
+    dst[i] = (kbl * kColBlocks + (r >> 4)) * 64 + q * 16 + (r & 15);
+    if (r < n_tok) {
+      if (NMAT == 2) {
+        const int p = a.t.sorted_pair[gd.begin + tok0 + r];
+        src[i] = reinterpret_cast<const uint16_t*>(a.x) + (size_t)(p / a.KS) * a.d + sg * 8;
+      } else {
+        src[i] = reinterpret_cast<const uint16_t*>(a.h) + (size_t)(gd.begin + tok0 + r) * a.f + sg * 8;
+      }
+    } else {
+      src[i] = nullptr;
+    }
+  }
+  auto load_x = [&](u32x4 (&xr)[4], int kb) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int kbi = kb + ((threadIdx.x + 256 * i) & 7) / 4;   // k-block this piece belongs to
+      xr[i] = (src[i] != nullptr && kbi < nkb) ? *reinterpret_cast<const u32x4*>(src[i] + (size_t)kb * 32)
+                                                : u32x4{0, 0, 0, 0};
+    }
+  };
+  auto load_w = [&](u32x4 (&wr)[kStageKb][NMAT], int kb) {
+#pragma unroll
+    for (int j = 0; j < kStageKb; ++j)
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+        wr[j][m] = kb + j < nkb ? __builtin_nontemporal_load(w + (size_t)(kb + j) * kb_stride + m * 64)
+                                : u32x4{0, 0, 0, 0};
+  };
+
+  f32x4 acc[kColBlocks][NMAT];
+#pragma unroll
+  for (int cb = 0; cb < kColBlocks; ++cb)
+#pragma unroll
+    for (int m = 0; m < NMAT; ++m) acc[cb][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  u32x4 xr[4], wc[kStageKb][NMAT], wn[kStageKb][NMAT];
+  load_x(xr, 0);
+  load_w(wc, 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) (&xs[0][0][0][0])[dst[i]] = xr[i];
+  __syncthreads();
+
+  int buf = 0;
+  for (int kb = 0; kb < nkb; kb += kStageKb) {
+    const bool more = kb + kStageKb < nkb;
+    if (more) {             // next stage's tokens and weights are fetched while this stage multiplies
+      load_x(xr, kb + kStageKb);
+      load_w(wn, kb + kStageKb);
+    }
+#pragma unroll
+    for (int j = 0; j < kStageKb; ++j) {
+#pragma unroll
+      for (int cb = 0; cb < kColBlocks; ++cb) {
+        if (cb < n_cb) {      // uniform
+          const bf16x8 bfrag = __builtin_bit_cast(bf16x8, xs[buf][j][cb][lane]);
+#pragma unroll
+          for (int m = 0; m < NMAT; ++m)
+            acc[cb][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wc[j][m]), bfrag,
+                                                                 acc[cb][m], 0, 0, 0);
+        }
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) (&xs[buf ^ 1][0][0][0])[dst[i]] = xr[i];
+#pragma unroll
+      for (int j = 0; j < kStageKb; ++j)
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m) wc[j][m] = wn[j][m];
+    }
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // ---- epilogue: lane holds rows (lane/16)*4 .. +3 of the row tile for token column lane%16 ----
+  if (!has_rows) return;
+  const int n = lane & 15, r4 = (lane >> 4) * 4;
+#pragma unroll
+  for (int cb = 0; cb < kColBlocks; ++cb) {
+    const int tk = cb * 16 + n;
+    if (cb < n_cb && tk < n_tok) {
+      const size_t pos = (size_t)(gd.begin + tok0 + tk);
+      if (NMAT == 2) {
+        uint16_t hv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) hv[i] = f32_to_bf16(silu(acc[cb][0][i]) * acc[cb][NMAT - 1][i]);
+        uint2 pk;
+        pk.x = (uint32_t)hv[0] | ((uint32_t)hv[1] << 16);
+        pk.y = (uint32_t)hv[2] | ((uint32_t)hv[3] << 16);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.h) + pos * a.f + rt * 16 + r4) = pk;
+      } else {
+        *reinterpret_cast<f32x4*>(a.o + pos * a.d + rt * 16 + r4) = acc[cb][0];
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, KernelEvents e2) {
+  if (a.g_max <= 0) return hipSuccess;
+  const int tiles = (a.max_count + kTokTile - 1) / kTokTile;
+  dim3 block(64 * kGemmWaves);
+  dim3 g1((a.f / 16 + kGemmWaves - 1) / kGemmWaves, a.g_max, tiles);
+  dim3 g2((a.d / 16 + kGemmWaves - 1) / kGemmWaves, a.g_max, tiles);
+  launch_timed(ffn_gemm_kernel<2>, g1, block, 0, s, e1, a);
+  launch_timed(ffn_gemm_kernel<1>, g2, block, 0, s, e2, a);
+  return hipGetLastError();
+}
+
+}  // namespace moe

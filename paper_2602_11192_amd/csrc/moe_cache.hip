@@ -540,13 +540,20 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   const bool tiled = cf.pool_layout == MOE_LAYOUT_TILED;
   const bool fused = tiled && ffn_fused_supported(d, cf.d_ff, batch);
   fa.fused = fused ? 1 : 0;
+  // Many tokens per expert: token tiles staged in LDS and shared by the waves of a row block.  Below about 32
+  // tokens per expert the split-K streaming kernels are faster (measured); the group sizes are not known to the
+  // host at launch, so the expected load batch * K / (experts that can be in use) decides.
+  const int experts_in_use = std::min(E, c->P);
+  const bool gemm = tiled && !fused && (int64_t)batch * K > (int64_t)24 * experts_in_use;
   const KernelEvents ke1 = ps ? ps->gate_up : KernelEvents{}, ke2 = ps ? ps->down : KernelEvents{};
 
   // Experts that were already resident: their FFN starts right behind the cache
   // lookups, before the host knows the miss list.
   fa.pass = 0;
   HIPCHK(fused ? launch_ffn_fused(s, fa, ke1)
-               : (tiled ? launch_ffn_tiled(s, fa, ke1, ke2) : launch_ffn_rowmajor(s, cf.dtype, fa, ke1, ke2)));
+         : gemm ? launch_ffn_gemm(s, fa, ke1, ke2)
+         : tiled ? launch_ffn_tiled(s, fa, ke1, ke2)
+                 : launch_ffn_rowmajor(s, cf.dtype, fa, ke1, ke2));
 
   HIPCHK(hipEventSynchronize(c->ev_mail));
   const uint32_t got = __atomic_load_n(&c->mailbox->seq, __ATOMIC_ACQUIRE);
@@ -562,8 +569,9 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
     c->copies_pending = false;
     fa.pass = 1;
     HIPCHK(fused ? launch_ffn_fused(s, fa, KernelEvents{})
-                 : (tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
-                          : launch_ffn_rowmajor(s, cf.dtype, fa, KernelEvents{}, KernelEvents{})));
+           : gemm ? launch_ffn_gemm(s, fa, KernelEvents{}, KernelEvents{})
+           : tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
+                   : launch_ffn_rowmajor(s, cf.dtype, fa, KernelEvents{}, KernelEvents{}));
   }
   if (ps) { ps->used = true; ps->mixed = mb.n_miss > 0; ps->fused = fused; }
   HIPCHK(fused ? launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev)

@@ -116,6 +116,7 @@ hipError_t launch_pin(hipStream_t s, const LayerState& st, const CallTables& t, 
 hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace);
 hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
+hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 bool ffn_fused_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 hipError_t launch_combine_chunks(hipStream_t s, const float* o_part, const float* wpair, const int32_t* pos_of,

@@ -180,6 +180,22 @@ def test_resident_batch_with_64_buffers_and_shared_experts(torch, P):
     cache.close()
 
 
+@pytest.mark.parametrize("n_experts,top_k,batch", [(16, 4, 128), (4, 2, 300), (8, 2, 97)])
+def test_many_tokens_per_expert_take_the_grouped_gemm(torch, P, n_experts, top_k, batch):
+    # enough tokens per expert for the LDS-staged grouped GEMM; 300 tokens over 4 experts need several
+    # 128-token tiles per expert with a ragged last tile
+    cfg = small_cfg(n_experts=n_experts, top_k=top_k, capacity=n_experts, n_seqs=batch, n_steps=2, n_layers=1,
+                    d_model=160, d_ff=96, n_shared=1, pref_lo=1, pref_hi=1)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=batch, trace_capacity=4096)
+    ost = OracleStack(wl, capacity=n_experts, keep=n_experts)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, list(range(batch)), step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_staging_exhausted_leaves_cache_unchanged(torch, P):
     from paper_2602_11192_amd import binding as B
     cfg = small_cfg(n_seqs=8, n_steps=4, n_layers=1, capacity=4, pref_lo=0, pref_hi=0, beta=0.0)

@@ -53,6 +53,15 @@ typedef enum {
 enum { MOE_DTYPE_FP32 = 0, MOE_DTYPE_BF16 = 1 };
 enum { MOE_POLICY_LRU = 0, MOE_POLICY_GAMMA = 1 };
 enum { MOE_LAYOUT_ROWMAJOR = 0, MOE_LAYOUT_TILED = 1 };
+/*
+ * MOE_FETCH_COPY_ENGINE  hipMemcpyAsync from the pinned pool on the library's copy stream, ordered by events
+ *                        before the FFN pass over the fetched experts; the FFN over resident experts overlaps it.
+ * MOE_FETCH_IN_KERNEL    decode calls of up to 16 tokens on the tiled bf16 layout: the expert kernel itself reads a
+ *                        missed expert from the pinned pool over PCIe while it computes, and fills the device
+ *                        buffer on the way; no copy engine and no host round trip on the miss path.  Calls the
+ *                        single-launch kernel does not cover, and prefill_pins, use the copy engine.
+ */
+enum { MOE_FETCH_COPY_ENGINE = 0, MOE_FETCH_IN_KERNEL = 1 };
 
 typedef struct moe_cache moe_cache_t; /* opaque; owned by the library */
 
@@ -82,7 +91,7 @@ typedef struct {
   int32_t device_id;       /* HIP device ordinal; -1 = the calling thread's current device  */
   int32_t trace_capacity;  /* lookup records kept per layer (0 = tracing off)               */
   int32_t pool_layout;     /* MOE_LAYOUT_*: layout of every expert block (see below)        */
-  int32_t reserved;        /* must be 0                                                     */
+  int32_t fetch_mode;      /* MOE_FETCH_*: how a missed expert reaches its device buffer    */
   double gamma;            /* decay of MOE_POLICY_GAMMA, in [0,1]; ignored for LRU          */
 } moe_cache_config_t;
 
@@ -127,6 +136,9 @@ typedef struct {
   double ffn_fused_ms;   /* summed duration of that kernel                                  */
   uint64_t route_launches; /* router + gating + cache-lookup launches timed                 */
   double route_ms;       /* their summed duration                                           */
+  uint64_t fetch_launches; /* in-kernel fetch: expert-FFN launches that also fetched experts */
+  uint64_t fetch_bytes;  /* bytes those launches brought in over PCIe                        */
+  double fetch_ms;       /* their summed duration (fetch and compute overlap inside them)   */
   uint64_t copies;       /* expert copies timed                                             */
   uint64_t copy_bytes;   /* bytes moved by them                                             */
   double copy_ms;        /* summed duration of the copy batches on the copy stream          */

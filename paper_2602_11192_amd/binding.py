@@ -26,6 +26,7 @@ MOE_ERR_TIMEOUT = -7
 MOE_DTYPE_FP32, MOE_DTYPE_BF16 = 0, 1
 MOE_POLICY_LRU, MOE_POLICY_GAMMA = 0, 1
 MOE_LAYOUT_ROWMAJOR, MOE_LAYOUT_TILED = 0, 1
+MOE_FETCH_COPY_ENGINE, MOE_FETCH_IN_KERNEL = 0, 1
 
 EXPORTS = ["moe_expert_bytes", "moe_pack_expert", "moe_cache_create", "moe_cache_destroy", "moe_cache_reset",
            "moe_cache_prefill_pins", "moe_layer_decode", "moe_cache_stats", "moe_cache_read_trace",
@@ -36,7 +37,7 @@ EXPORTS = ["moe_expert_bytes", "moe_pack_expert", "moe_cache_create", "moe_cache
 class moe_cache_config_t(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_experts", "n_shared", "top_k", "d_model", "d_ff", "capacity", "dtype", "norm_topk",
-        "policy", "max_batch", "staging_buffers", "device_id", "trace_capacity", "pool_layout", "reserved")
+        "policy", "max_batch", "staging_buffers", "device_id", "trace_capacity", "pool_layout", "fetch_mode")
     ] + [("gamma", C.c_double)]
 
 
@@ -56,6 +57,7 @@ class moe_timing_t(C.Structure):
     _fields_ = [("ffn_launches", C.c_uint64), ("ffn_gate_up_ms", C.c_double), ("ffn_down_ms", C.c_double),
                 ("ffn_fused_launches", C.c_uint64), ("ffn_fused_ms", C.c_double),
                 ("route_launches", C.c_uint64), ("route_ms", C.c_double),
+                ("fetch_launches", C.c_uint64), ("fetch_bytes", C.c_uint64), ("fetch_ms", C.c_double),
                 ("copies", C.c_uint64), ("copy_bytes", C.c_uint64), ("copy_ms", C.c_double)]
 
 
@@ -146,10 +148,11 @@ class MoECache:
 
     def __init__(self, *, n_layers, n_experts, top_k, d_model, d_ff, capacity, dtype, router_w, expert_pool,
                  shared_w=None, n_shared=0, norm_topk=1, policy=MOE_POLICY_LRU, gamma=1.0, max_batch=1,
-                 staging_buffers=0, device_id=-1, trace_capacity=0, pool_layout=MOE_LAYOUT_ROWMAJOR):
+                 staging_buffers=0, device_id=-1, trace_capacity=0, pool_layout=MOE_LAYOUT_ROWMAJOR,
+                 fetch_mode=MOE_FETCH_COPY_ENGINE):
         self.cfg = moe_cache_config_t(n_layers, n_experts, n_shared, top_k, d_model, d_ff, capacity, dtype,
                                       norm_topk, policy, max_batch, staging_buffers, device_id, trace_capacity,
-                                      pool_layout, 0, float(gamma))
+                                      pool_layout, fetch_mode, float(gamma))
         self._keep = (router_w, expert_pool, shared_w)
         w = moe_weights_t(_ptr(router_w), _ptr(expert_pool), _ptr(shared_w))
         self._h = C.c_void_p()

@@ -76,7 +76,16 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
   const int kb0 = ks, kb_step = KS;
 
   const size_t x_step = (size_t)kb_step * 32, w_step = (size_t)kb_step * 128;
-  const u32x4* wbase = reinterpret_cast<const u32x4*>(group_weights(a, gd.buf));
+  // a group whose expert is not resident yet reads it from the pinned host pool over PCIe and, on the way,
+  // fills its device buffer for the calls to come (fetch fused into the compute: no copy engine, no host)
+  const bool from_host = a.fetch != 0 && gd.miss != 0;
+  const char* wdev = group_weights(a, gd.buf);
+  const char* wsrc = from_host ? a.pool + (size_t)gd.expert * a.expert_bytes : wdev;
+  const intptr_t fill_delta = reinterpret_cast<intptr_t>(wdev) - reinterpret_cast<intptr_t>(wsrc);
+  const u32x4* wbase = reinterpret_cast<const u32x4*>(wsrc);
+  auto fill = [&](const u32x4* src, u32x4 v) {     // same offset inside the device block
+    *reinterpret_cast<u32x4*>(reinterpret_cast<intptr_t>(src) + fill_delta) = v;
+  };
   // gate/up fragment (row tile 2c+tile, kb, m) and W_d fragment (chunk c, row tile dt)
   const u32x4* wa = wbase + ((size_t)(2 * c + tile) * nkb_d + kb0) * 2 * 64 + lane;
   const u32x4* wb = wbase + (size_t)2 * a.f * d / 8 + ((size_t)c * n_dt + wave) * 64 + lane;
@@ -112,6 +121,10 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
         const bf16x8 xb = __builtin_bit_cast(bf16x8, sx[u]);
         accg = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, sg[u]), xb, accg, 0, 0, 0);
         accu = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, su[u]), xb, accu, 0, 0, 0);
+        if (from_host) {
+          fill(wa + (size_t)(base + u) * w_step, sg[u]);
+          fill(wa + (size_t)(base + u) * w_step + 64, su[u]);
+        }
         issue(u, base + u + kDepth);
       }
     }
@@ -148,6 +161,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
         const int v = (SLOT0 + u) % kDepth;   // compile-time after unrolling
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, sg[v]), hb, acc, 0, 0, 0);
+        if (from_host) fill(wb + (size_t)j * WAVES * 64, sg[v]);
         issue(v, na + j + kDepth);
         // lane holds rows (lane/16)*4 .. +3 of row tile (wave + WAVES j) for token n
         if (n < cnt)

@@ -49,6 +49,7 @@ struct ProfSlot {
   bool used = false;
   bool mixed = false;  // the call also fetched experts: its resident-pass FFN covers only part of the K experts
   bool fused = false;  // the call used the single-launch decode FFN (timed by `gate_up`)
+  uint64_t fetched = 0; // bytes that launch read from the host pool (in-kernel fetch)
 };
 struct CopySlot {
   hipEvent_t c0 = nullptr, c1 = nullptr;
@@ -75,6 +76,7 @@ struct moe_cache {
   void* h = nullptr;
   float* o = nullptr;
   int32_t* arrive = nullptr;
+  const char* pool_dev = nullptr;   // the pinned pool as the device sees it (in-kernel fetch)
 
   char* host_mem = nullptr;       // pinned: mailbox | pin ids | miss list
   Mailbox* mailbox = nullptr;
@@ -135,7 +137,8 @@ int validate(const moe_cache_config_t* c, const moe_weights_t* w) {
   if (c->trace_capacity < 0) return fail(MOE_ERR_INVALID_ARG, "trace_capacity must be >= 0");
   if (c->pool_layout != MOE_LAYOUT_ROWMAJOR && c->pool_layout != MOE_LAYOUT_TILED)
     return fail(MOE_ERR_INVALID_ARG, "unknown pool_layout");
-  if (c->reserved != 0) return fail(MOE_ERR_INVALID_ARG, "reserved must be 0");
+  if (c->fetch_mode != MOE_FETCH_COPY_ENGINE && c->fetch_mode != MOE_FETCH_IN_KERNEL)
+    return fail(MOE_ERR_INVALID_ARG, "unknown fetch_mode");
   if (c->capacity < 1) return fail(MOE_ERR_INVALID_ARG, "capacity must be >= 1");
   if (c->capacity < c->top_k)
     return fail(MOE_ERR_CAPACITY_LT_TOPK, "capacity %d < top_k %d: one token's experts would not fit", c->capacity,
@@ -146,6 +149,8 @@ int validate(const moe_cache_config_t* c, const moe_weights_t* w) {
   const int vec = c->dtype == MOE_DTYPE_FP32 ? 4 : 8;
   if (c->d_model % vec != 0)
     return fail(MOE_ERR_UNSUPPORTED, "d_model must be a multiple of %d for this dtype", vec);
+  if (c->fetch_mode == MOE_FETCH_IN_KERNEL && (c->pool_layout != MOE_LAYOUT_TILED || c->dtype != MOE_DTYPE_BF16))
+    return fail(MOE_ERR_UNSUPPORTED, "in-kernel fetch needs the tiled bf16 layout");
   if (c->pool_layout == MOE_LAYOUT_TILED) {
     if (c->dtype != MOE_DTYPE_BF16) return fail(MOE_ERR_UNSUPPORTED, "the tiled layout is bf16 only");
     if (c->d_model % 32 != 0 || c->d_ff % 32 != 0)
@@ -237,6 +242,11 @@ int drain_prof_slot(moe_cache* c, ProfSlot& p) {
   if (!p.fused) HIPCHK(hipEventElapsedTime(&b, p.down.start, p.down.stop));
   c->timing.route_ms += r;
   c->timing.route_launches += 1;
+  if (p.fetched) {
+    c->timing.fetch_launches += 1;
+    c->timing.fetch_bytes += p.fetched;
+    c->timing.fetch_ms += a;
+  }
   if (!p.mixed) {
     if (p.fused) {
       c->timing.ffn_fused_ms += a;
@@ -414,6 +424,17 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->pin_ids = reinterpret_cast<int32_t*>(c->host_mem + align_up(sizeof(Mailbox), 64));
   c->miss_list = reinterpret_cast<MissEntry*>(c->host_mem + align_up(sizeof(Mailbox), 64) + align_up((size_t)C * 4, 64));
 
+  if (cfg->fetch_mode == MOE_FETCH_IN_KERNEL) {
+    void* dp = nullptr;
+    hipError_t e_ = hipHostGetDevicePointer(&dp, const_cast<void*>(weights->expert_pool), 0);
+    if (e_ != hipSuccess || dp == nullptr) {
+      (void)hipGetLastError();
+      free_all(c);
+      return fail(MOE_ERR_UNSUPPORTED, "in-kernel fetch: expert_pool is not device-visible pinned host memory (%s)",
+                  hipGetErrorString(e_));
+    }
+    c->pool_dev = static_cast<const char*>(dp);
+  }
   CREATE_CHK(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking), MOE_ERR_HIP);
   CREATE_CHK(hipEventCreateWithFlags(&c->ev_mail, hipEventDisableTiming), MOE_ERR_HIP);
   CREATE_CHK(hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming), MOE_ERR_HIP);
@@ -548,8 +569,12 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   const KernelEvents ke1 = ps ? ps->gate_up : KernelEvents{}, ke2 = ps ? ps->down : KernelEvents{};
 
   // Experts that were already resident: their FFN starts right behind the cache
-  // lookups, before the host knows the miss list.
-  fa.pass = 0;
+  // lookups, before the host knows the miss list.  With in-kernel fetch the same
+  // launch also streams the missed experts from the host pool.
+  const bool in_kernel = fused && cf.fetch_mode == MOE_FETCH_IN_KERNEL;
+  fa.pool = in_kernel ? c->pool_dev + (size_t)layer * E * c->expert_bytes : nullptr;
+  fa.fetch = in_kernel ? 1 : 0;
+  fa.pass = in_kernel ? 2 : 0;
   HIPCHK(fused ? launch_ffn_fused(s, fa, ke1)
          : gemm ? launch_ffn_gemm(s, fa, ke1, ke2)
          : tiled ? launch_ffn_tiled(s, fa, ke1, ke2)
@@ -562,7 +587,7 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   if (mb.status != MOE_OK)
     return fail(mb.status, "call needs more spare expert buffers than staging_buffers=%d (batch %d)",
                 cf.staging_buffers, batch);
-  if (mb.n_miss > 0) {
+  if (mb.n_miss > 0 && !in_kernel) {
     int rc = issue_copies(c, layer, mb.n_miss);
     if (rc != MOE_OK) return rc;
     HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0));
@@ -573,7 +598,10 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
            : tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
                    : launch_ffn_rowmajor(s, cf.dtype, fa, KernelEvents{}, KernelEvents{}));
   }
-  if (ps) { ps->used = true; ps->mixed = mb.n_miss > 0; ps->fused = fused; }
+  if (ps) {
+    ps->used = true; ps->mixed = mb.n_miss > 0; ps->fused = fused;
+    ps->fetched = in_kernel ? (uint64_t)mb.n_miss * c->expert_bytes : 0;
+  }
   HIPCHK(fused ? launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev)
                : launch_combine(s, cf.dtype, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, y_dev));
 

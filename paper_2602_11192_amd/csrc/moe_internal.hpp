@@ -47,7 +47,8 @@ struct __attribute__((aligned(32))) GroupDesc {
   int32_t count;   // pairs in the group
   int32_t miss;    // 1 if the buffer is being filled by this call
   int32_t pair0;   // sorted_pair[begin], the group's first pair (its token is pair0 / KS)
-  int32_t pad[3];
+  int32_t expert;  // miss == 1: the expert being brought into the buffer; else -1
+  int32_t pad[2];
 };
 
 // Per-call scratch tables (device).
@@ -87,6 +88,8 @@ struct FfnArgs {
   float* o;                // [B*KS][d]; fused path: partial sums [pairs][f/32][d]
   int32_t fused;           // 1: o holds per-chunk partial sums (fused decode kernel)
   int32_t pass;            // 0: groups whose buffer was resident, 1: groups fetched by this call, 2: all
+  const char* pool;        // in-kernel fetch: this layer's expert blocks in pinned host memory (device-visible)
+  int32_t fetch;           // 1: groups with miss == 1 read their weights from `pool` and fill their buffer
 };
 
 // Router inputs of one call.

@@ -241,8 +241,9 @@ __device__ int group_pairs_lds(int32_t* count, int32_t* cursor, const int32_t* f
     const uint64_t gm = __ballot(c > 0);
     if (c > 0) {
       GroupDesc gd;
-      gd.buf = id; gd.begin = begin; gd.count = c; gd.miss = id < P ? filled[id] : 0;
-      gd.pair0 = 0; gd.pad[0] = gd.pad[1] = gd.pad[2] = 0;
+      const int fe = id < P ? filled[id] : 0;        // expert + 1 of a buffer being filled by this call
+      gd.buf = id; gd.begin = begin; gd.count = c; gd.miss = fe != 0;
+      gd.pair0 = 0; gd.expert = fe - 1; gd.pad[0] = gd.pad[1] = 0;
       t.grp[n_groups + __popcll(gm & lt_mask)] = gd;
     }
     if (id < NB) cursor[id] = begin;
@@ -376,7 +377,7 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
         expert_in[s] = e;
         slot_of[e] = s;
         buf_of_slot[s] = buf;
-        filled[buf] = 1;
+        filled[buf] = e + 1;
         if (n_miss < a.max_miss) a.miss_list[n_miss] = MissEntry{e, buf};
       }
       ++n_miss;
@@ -527,42 +528,61 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
   const bool small = NP <= kWave;     // all pairs fit one per lane
   int status = MOE_OK, n_miss = 0, n_evict = 0, n_hits = 0;
   int my_pair = -1;       // small calls: lane p = b*KS + k holds the buffer the pair reads
-  bool filled = false;    // lane p: buffer p is being filled by this call
+  int filled = 0;         // lane p: expert + 1 that this call brings into buffer p, 0 if none
   PHASE_TS(4);
 
-  for (int chunk0 = 0; chunk0 < n_lookups && status == MOE_OK; chunk0 += kWave) {
+  // ---- shortcut for a call whose lookups all hit (the resident regime): residency does not change, and the
+  //      recency updates commute - the last lookup of a slot decides its tick.  Lookups run 64 per step. ----
+  bool all_hit = false;
+  if (a.mode == 0 && f.n_res > 0 && n_lookups >= 16) {     // for a handful of lookups the in-order loop is cheaper
+    for (int e = lane; e < a.E; e += kWave) lds_slot_of[e] = -1;
+    if (lane < P) { lds_last[lane] = 0; lds_touch[lane] = 0; }
+    wave_sync();
+    if (lane < C && f.exp >= 0) lds_slot_of[f.exp] = lane;
+    wave_sync();
+    uint64_t any_miss = 0;
+    for (int chunk0 = 0; chunk0 < n_lookups; chunk0 += kWave) {
+      const bool valid = chunk0 + lane < n_lookups;
+      any_miss |= __ballot(valid && lds_slot_of[idx_src[chunk0 + lane]] < 0);
+    }
+    all_hit = any_miss == 0;
+  }
+  if (all_hit) {
+    for (int chunk0 = 0; chunk0 < n_lookups; chunk0 += kWave) {
+      const int l = chunk0 + lane;
+      const bool valid = l < n_lookups;
+      const int my_e = valid ? idx_src[l] : 0;
+      const int my_slot = valid ? lds_slot_of[my_e] : 0;
+      if (valid) atomicMax(&lds_last[my_slot], l + 1);
+      const int my_buf = __shfl(f.buf, my_slot);
+      if (valid && f.trace_n + l < a.trace_cap) st.trace[f.trace_n + l] = moe_trace_rec_t{l / K, my_e, 1, -1};
+      if (small) {
+        // lane p = b*KS + k takes the buffer of lookup b*K + k (a single step)
+        const int b = lane / KS, k = lane - b * KS;
+        const int v = __shfl(my_buf, k < K ? b * K + k : 0);
+        if (lane < NP && k < K) my_pair = v;
+      } else if (valid) {
+        const int b = l / K;
+        pair_buf[(size_t)b * KS + (l - b * K)] = my_buf;
+      }
+    }
+    wave_sync();
+    const int last = lane < C ? lds_last[lane] : 0;
+    if (last > 0) {
+      f.tick = (uint64_t)(f.clock + last);
+      lds_touch[f.buf] = 1;
+    }
+    wave_sync();
+    if (lane < P && lds_touch[lane]) f.used = seq;
+    f.clock += n_lookups;
+    n_hits = n_lookups;
+  }
+
+  for (int chunk0 = 0; chunk0 < n_lookups && status == MOE_OK && !all_hit; chunk0 += kWave) {
     const int nl = min(kWave, n_lookups - chunk0);
     const int my_e = lane < nl ? idx_src[chunk0 + lane] : -3;
     int my_buf = -1;      // lane q: buffer that lookup chunk0 + q reads
-    bool done = false;
-    if (a.mode == 0 && f.n_res > 0 && nl >= 16) {     // for a handful of lookups the in-order loop is cheaper
-      // ---- shortcut: if every lookup of the chunk hits, residency does not change inside the chunk and
-      //      the recency updates commute: the last lookup of a slot decides its tick ----
-      for (int e = lane; e < a.E; e += kWave) lds_slot_of[e] = -1;
-      if (lane < P) { lds_last[lane] = 0; lds_touch[lane] = 0; }
-      wave_sync();
-      if (lane < C && f.exp >= 0) lds_slot_of[f.exp] = lane;
-      wave_sync();
-      const int my_slot = lane < nl ? lds_slot_of[my_e] : -1;
-      if (__ballot(lane < nl && my_slot < 0) == 0) {
-        if (lane < nl) atomicMax(&lds_last[my_slot], lane + 1);
-        wave_sync();
-        const int last = lane < C ? lds_last[lane] : 0;
-        if (last > 0) {
-          f.tick = (uint64_t)(f.clock + last);
-          lds_touch[f.buf] = 1;
-        }
-        wave_sync();
-        if (lane < P && lds_touch[lane]) f.used = seq;
-        my_buf = __shfl(f.buf, my_slot < 0 ? 0 : my_slot);
-        if (lane < nl && f.trace_n + chunk0 + lane < a.trace_cap)
-          st.trace[f.trace_n + chunk0 + lane] = moe_trace_rec_t{(chunk0 + lane) / K, my_e, 1, -1};
-        f.clock += nl;
-        n_hits += nl;
-        done = true;
-      }
-    }
-    if (!done) {
+    {
       for (int q = 0; q < nl; ++q) {
         const int e = readlane_i(my_e, q);
         const uint64_t hm = __ballot(f.exp == e);
@@ -591,7 +611,7 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
             ++n_evict;
           }
           if (lane == s) { f.exp = e; f.buf = buf; }
-          if (lane == buf) filled = true;
+          if (lane == buf) filled = e + 1;
           if (lane == 0 && n_miss < a.max_miss) a.miss_list[n_miss] = MissEntry{e, buf};
           ++n_miss;
         }
@@ -639,22 +659,23 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
         const int q = __ffsll((unsigned long long)m) - 1;
         gidx += readlane_i(my_pair, q) < my_pair ? 1 : 0;
       }
-      const int was_filled = __shfl((int)filled, my_pair < P && my_pair >= 0 ? my_pair : 0);
+      const int was_filled = __shfl(filled, my_pair < P && my_pair >= 0 ? my_pair : 0);
       if (lane < NP) {
         t.sorted_pair[rank] = lane;
         t.pos_of[lane] = rank;
         if (is_first) {
           GroupDesc gd;
-          gd.buf = my_pair; gd.begin = rank; gd.count = cnt; gd.miss = my_pair < P ? was_filled : 0;
+          const int fe = my_pair < P ? was_filled : 0;
+          gd.buf = my_pair; gd.begin = rank; gd.count = cnt; gd.miss = fe != 0;
           gd.pair0 = lane;      // stable order: the group's first pair is its lowest pair id
-          gd.pad[0] = gd.pad[1] = gd.pad[2] = 0;
+          gd.expert = fe - 1; gd.pad[0] = gd.pad[1] = 0;
           t.grp[gidx] = gd;
         }
       }
       n_groups = __popcll(fm);
     } else {
       // ---- more than 64 pairs: counting sort with the counters in LDS ----
-      if (lane < P) lds_filled[lane] = filled ? 1 : 0;
+      if (lane < P) lds_filled[lane] = filled;
       wave_sync();
       n_groups = group_pairs_lds(lds_count, lds_cursor, lds_filled, pair_buf, t, a);
     }

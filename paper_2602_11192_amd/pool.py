@@ -74,7 +74,8 @@ def build_shared(wl, tiled: bool, device="cuda:0"):
 
 
 def make_cache(wl, *, tiled=None, capacity=None, max_batch=1, staging_buffers=0, trace_capacity=0,
-               policy=B.MOE_POLICY_LRU, gamma=1.0, norm_topk=None, device="cuda:0", pool=None):
+               policy=B.MOE_POLICY_LRU, gamma=1.0, norm_topk=None, device="cuda:0", pool=None,
+               fetch_mode=B.MOE_FETCH_COPY_ENGINE):
     """Build pool + router (+ shared) for `wl` and create the native cache."""
     cfg = wl.cfg
     if tiled is None:
@@ -88,6 +89,6 @@ def make_cache(wl, *, tiled=None, capacity=None, max_batch=1, staging_buffers=0,
         dtype=moe_dtype(cfg), norm_topk=cfg.norm_topk if norm_topk is None else norm_topk, policy=policy,
         gamma=gamma, max_batch=max_batch, staging_buffers=staging_buffers,
         device_id=torch.device(device).index or 0, trace_capacity=trace_capacity,
-        pool_layout=B.MOE_LAYOUT_TILED if tiled else B.MOE_LAYOUT_ROWMAJOR,
+        pool_layout=B.MOE_LAYOUT_TILED if tiled else B.MOE_LAYOUT_ROWMAJOR, fetch_mode=fetch_mode,
         router_w=router, expert_pool=pool, shared_w=shared)
     return cache

@@ -49,7 +49,7 @@ def test_expert_bytes(B):
 def good_cfg(B, **kw):
     f = dict(n_layers=1, n_experts=8, n_shared=0, top_k=2, d_model=64, d_ff=128, capacity=2, dtype=B.MOE_DTYPE_FP32,
              norm_topk=1, policy=B.MOE_POLICY_LRU, max_batch=1, staging_buffers=0, device_id=-1, trace_capacity=0,
-             pool_layout=B.MOE_LAYOUT_ROWMAJOR, reserved=0, gamma=1.0)
+             pool_layout=B.MOE_LAYOUT_ROWMAJOR, fetch_mode=0, gamma=1.0)
     f.update(kw)
     return B.moe_cache_config_t(**f)
 
@@ -69,7 +69,8 @@ def create(B, cfg, router=0x1000, pool=0x2000, shared=None):
     (dict(capacity=0), "MOE_ERR_INVALID_ARG"), (dict(dtype=3), "MOE_ERR_INVALID_ARG"),
     (dict(policy=5), "MOE_ERR_INVALID_ARG"), (dict(policy=1, gamma=1.5), "MOE_ERR_INVALID_ARG"),
     (dict(max_batch=0), "MOE_ERR_INVALID_ARG"), (dict(staging_buffers=-1), "MOE_ERR_INVALID_ARG"),
-    (dict(trace_capacity=-1), "MOE_ERR_INVALID_ARG"), (dict(reserved=1), "MOE_ERR_INVALID_ARG"),
+    (dict(trace_capacity=-1), "MOE_ERR_INVALID_ARG"), (dict(fetch_mode=2), "MOE_ERR_INVALID_ARG"),
+    (dict(fetch_mode=1), "MOE_ERR_UNSUPPORTED"),               # in-kernel fetch needs the tiled bf16 layout
     (dict(pool_layout=1), "MOE_ERR_UNSUPPORTED"),              # tiled needs bf16
     (dict(dtype=1, pool_layout=1, d_ff=100), "MOE_ERR_UNSUPPORTED"),
     (dict(d_model=66), "MOE_ERR_UNSUPPORTED"), (dict(norm_topk=2), "MOE_ERR_INVALID_ARG"),

@@ -58,6 +58,18 @@ def test_olmoe_like_full_workload_sequence_serial(torch, P, olmoe):
     cache.close()
 
 
+def test_olmoe_like_in_kernel_fetch(torch, P, olmoe):
+    from paper_2602_11192_amd import binding as B
+    wl, pool = olmoe
+    cfg = wl.cfg
+    cache = P.make_cache(wl, pool=pool, trace_capacity=6 * cfg.n_steps * cfg.top_k, fetch_mode=B.MOE_FETCH_IN_KERNEL)
+    ost = OracleStack(wl, keep=cfg.n_experts)
+    worst, n_y, traces = run_sequence_serial(wl, cache, ost, torch=torch, y_every=8, seqs=[0, 3, 7, 8, 12, 15])
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    assert cache.moe_cache_stats()["misses"] > 100
+    cache.close()
+
+
 def test_olmoe_like_cold_start_without_prefetch(torch, P, olmoe):
     wl, pool = olmoe
     cfg = wl.cfg

@@ -122,6 +122,27 @@ def test_single_launch_decode_ffn_shapes(torch, P, d_model, d_ff, batch):
     cache.close()
 
 
+@pytest.mark.parametrize("batch", [1, 3, 7])
+def test_in_kernel_fetch_matches_oracle(torch, P, batch):
+    # missed experts are read from the pinned pool by the expert kernel itself and land in their buffers
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(n_seqs=7, n_steps=12, n_layers=2, capacity=5 if batch > 1 else 6, d_model=256, d_ff=96, beta=1.0)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=batch, staging_buffers=batch * cfg.top_k if batch > 1 else 0,
+                         trace_capacity=8192, fetch_mode=B.MOE_FETCH_IN_KERNEL)
+    ost = OracleStack(wl)
+    if batch == 1:
+        _, _, traces = run_sequence_serial(wl, cache, ost, torch=torch, seqs=[0, 1, 2], pins=False)
+    else:
+        traces = [[], []]
+        for step in range(cfg.n_steps):
+            for l in range(2):
+                traces[l].extend(batched_step(torch, P, wl, cache, ost, l, list(range(batch)), step))
+    assert cache.moe_cache_stats()["misses"] > 10
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_lru_table_larger_than_a_wave(torch, P):
     # capacity above 64 slots: the cache table is staged in LDS instead of registers
     cfg = small_cfg(n_experts=96, capacity=70, n_layers=1, n_seqs=2, n_steps=40, pref_lo=0, pref_hi=0, beta=0.0)

@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fetch-mode", choices=["copy_engine", "in_kernel"], default="in_kernel",
                     help="how missed experts reach the device (see MOE_FETCH_* in include/moe_cache.h)")
+    ap.add_argument("--batch-sweep", metavar="FILE", default=None,
+                    help="also time the resident path at batch 1..1024 and write the table to FILE (JSON)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain 256 MiB copy kernel (reference dispatch for profiler memory counters)")
     return ap.parse_args()
@@ -100,6 +102,45 @@ def timed(torch, fn, steps):
         n += fn()
     torch.cuda.synchronize()
     return n, time.perf_counter() - t0
+
+
+def batch_sweep(torch, P, wl, pool, sizes=(1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024), reps=20):
+    """Resident path (capacity = E) at growing batch: tokens/s, kernel times, matrix-core rate of the FFN."""
+    import numpy as np
+    cfg = wl.cfg
+    toks = np.concatenate([wl.tokens(s) for s in range(cfg.n_seqs)])
+    bias = np.concatenate([np.tile(wl.bias(0, s), (cfg.n_steps, 1)) for s in range(cfg.n_seqs)])
+    rows = []
+    for bsz in sizes:
+        if bsz > toks.shape[0]:
+            break
+        cache = P.make_cache(wl, tiled=True, pool=pool, capacity=cfg.n_experts, max_batch=bsz)
+        cache.moe_cache_prefill_pins(0, list(range(cfg.n_experts)))
+        x = P.to_device(toks[:bsz])
+        b = torch.from_numpy(bias[:bsz].copy()).cuda()
+        y = torch.empty((bsz, cfg.d_model), dtype=P.torch_dtype(cfg), device="cuda:0")
+        for _ in range(3):
+            cache.moe_layer_decode(0, x, y, b)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            cache.moe_layer_decode(0, x, y, b)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / reps
+        cache.moe_cache_set_profiling(True)
+        cache.moe_cache_timing(clear=True)
+        for _ in range(reps):
+            cache.moe_layer_decode(0, x, y, b)
+        tm = cache.moe_cache_timing(clear=True)
+        n = max(1, tm["ffn_launches"] + tm["ffn_fused_launches"])
+        ffn_us = (tm["ffn_gate_up_ms"] + tm["ffn_down_ms"] + tm["ffn_fused_ms"]) / n * 1e3
+        flops = 6.0 * cfg.d_model * cfg.d_ff * bsz * (cfg.top_k + cfg.n_shared)
+        rows.append({"batch": bsz, "call_us": dt * 1e6, "tokens_per_s": bsz / dt,
+                     "route_cache_us": tm["route_ms"] / max(1, tm["route_launches"]) * 1e3, "ffn_us": ffn_us,
+                     "ffn_TFLOPs": flops / ffn_us / 1e6,
+                     "ffn_kernel": "single-launch decode" if tm["ffn_fused_launches"] else "two kernels"})
+        cache.close()
+    return {"workload": cfg.name, "layer": 0, "capacity": cfg.n_experts, "rows": rows}
 
 
 def cpu_baseline(wl, n_tokens):
@@ -189,6 +230,22 @@ def main():
     cache.moe_cache_set_profiling(False)
     cache.close()
 
+    # the same workload with the copy-engine fetch (hipMemcpyAsync on the copy stream), for comparison
+    other = None
+    if a.fetch_mode == "in_kernel":
+        ocache = P.make_cache(wl, tiled=True, pool=pool, fetch_mode=P.B.MOE_FETCH_COPY_ENGINE)
+        orun = Runner(wl, ocache, torch, P)
+        orun.pass_sequence_serial()
+        n_o, dt_o = timed(torch, orun.pass_sequence_serial, max(1, a.steps // 2))
+        ocache.moe_cache_set_profiling(True)
+        ocache.moe_cache_timing(clear=True)
+        timed(torch, orun.pass_sequence_serial, 1)
+        otm = ocache.moe_cache_timing(clear=True)
+        ocache.close()
+        other = {"tokens_per_s": n_o / dt_o,
+                 "pcie_GBps": otm["copy_bytes"] / (otm["copy_ms"] * 1e-3) / 1e9 if otm["copy_ms"] > 0 else None,
+                 "note": "fetch_mode copy_engine: hipMemcpyAsync per missed expert on the library's copy stream"}
+
     # ---------------- resident path: every expert on the device ----------------
     rcache = P.make_cache(wl, tiled=True, pool=pool, capacity=cfg.n_experts)
     rrun = Runner(wl, rcache, torch, P)
@@ -258,9 +315,12 @@ def main():
                           "frac_of_hbm_peak_whole_call": layer_bytes * cfg.n_layers * res_tok_s / 1e9 / HBM_PEAK_GBPS,
                           "ffn_kernels_us": ffn_ms_r * 1e3,
                           "route_cache_us": rtm["route_ms"] / max(1, rtm["route_launches"]) * 1e3},
+        "copy_engine_fetch": other,
         "profiled_rerun_tokens_per_s": n_tok_p / dt_p,
         "setup_s": t_gen,
     }
+    if a.batch_sweep:
+        json.dump(batch_sweep(torch, P, wl, pool), open(a.batch_sweep, "w"), indent=1)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, a.cpu_baseline_tokens)
     print(json.dumps(out))

@@ -108,8 +108,9 @@ def batch_sweep(torch, P, wl, pool, sizes=(1, 2, 4, 8, 16, 32, 64, 128, 256, 512
     """Resident path (capacity = E) at growing batch: tokens/s, kernel times, matrix-core rate of the FFN."""
     import numpy as np
     cfg = wl.cfg
-    toks = np.concatenate([wl.tokens(s) for s in range(cfg.n_seqs)])
-    bias = np.concatenate([np.tile(wl.bias(0, s), (cfg.n_steps, 1)) for s in range(cfg.n_seqs)])
+    # row i of a batch is step i // S of sequence i % S: a batch takes one token of every sequence, then wraps
+    toks = np.stack([wl.tokens(s) for s in range(cfg.n_seqs)], axis=1).reshape(-1, cfg.d_model)
+    bias = np.tile(np.stack([wl.bias(0, s) for s in range(cfg.n_seqs)]), (cfg.n_steps, 1))
     rows = []
     for bsz in sizes:
         if bsz > toks.shape[0]:
@@ -188,6 +189,8 @@ def main():
               file=sys.stderr)
         sys.exit(2)
     import torch
+    from paper_2602_11192_amd.build import ensure_built
+    ensure_built()
     from paper_2602_11192_amd import pool as P
     from workload import Workload, get_config
     assert torch.cuda.is_available(), "bench.py needs the GPU"

@@ -39,5 +39,10 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only if no library is there (tests, smoke and the benchmark load what is built)."""
+    return LIB if os.path.exists(LIB) else build_library()
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))

@@ -8,3 +8,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the shared libraries are build products (not in the history): build them once if they are not there
+    from paper_2602_11192_amd.build import ensure_built
+    ensure_built()
+    import oracle
+    oracle.build()

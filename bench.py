@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="olmoe_like")
+    ap.add_argument("--layers", type=int, default=None, help="cut the layer stack of the workload to this many layers")
+    ap.add_argument("--seqs", type=int, default=None, help="use only this many sequences")
+    ap.add_argument("--decode-steps", type=int, default=None, help="decode steps per sequence")
     ap.add_argument("--cpu-baseline-tokens", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fetch-mode", choices=["copy_engine", "in_kernel"], default="in_kernel",
@@ -204,6 +207,12 @@ def main():
         del src, dst
 
     cfg = get_config(a.workload)
+    if a.layers:
+        cfg = cfg.with_(n_layers=a.layers)
+    if a.seqs:
+        cfg = cfg.with_(n_seqs=a.seqs)
+    if a.decode_steps:
+        cfg = cfg.with_(n_steps=a.decode_steps)
     wl = Workload(cfg)
     t0 = time.perf_counter()
     pool = P.build_pool(wl, tiled=True)

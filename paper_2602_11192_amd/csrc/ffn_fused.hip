@@ -172,10 +172,10 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
 }
 
 // y[b][i] = sum_j wpair[b][j] * sum_c o_part[pos_of[b][j]][c][i].
-// A workgroup owns 32 columns of one token; its 32 slices split the KS * n_chunks
+// A workgroup owns 16 columns of one token; its 64 slices split the KS * n_chunks
 // terms (every load issued before the first use), then the slices are summed in
 // slice order: the result does not depend on timing.
-constexpr int kCombCols = 32, kCombSlices = 32, kCombItems = 8;
+constexpr int kCombCols = 16, kCombSlices = 64, kCombItems = 16;
 
 template <typename T>
 __global__ void __launch_bounds__(kCombCols * kCombSlices)

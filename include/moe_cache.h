@@ -117,6 +117,8 @@ typedef struct {
   uint64_t evictions; /* resident experts dropped to make room (decode and prefill_pins)    */
   uint64_t pin_loads; /* expert copies issued by moe_cache_prefill_pins                     */
   uint64_t bytes_h2d; /* (misses + pin_loads) * expert_bytes                                */
+  uint64_t stream_loads;   /* experts read from the host pool by moe_layer_prefill, not inserted */
+  uint64_t bytes_streamed; /* stream_loads * expert_bytes                                    */
 } moe_cache_stats_t;
 
 /* One lookup, in the order the lookups were made. */
@@ -199,6 +201,19 @@ int moe_cache_prefill_pins(moe_cache_t* cache, int32_t layer, const int32_t* exp
 int moe_layer_decode(moe_cache_t* cache, int32_t layer, const void* x_dev,
                      const float* logit_bias_dev, int32_t batch, void* y_dev,
                      int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
+
+/*
+ * Prompt processing in streaming mode.  The paper places the prefetch "before generation begins"
+ * (section 3.2) and does not say how the prompt's own MoE layers meet the cache; the reading taken here: the
+ * n_tokens prompt tokens go through the layer in one call (Eq. 1-3 as in moe_layer_decode), experts that are
+ * resident are read from their buffers, every other selected expert is read straight from the pinned host pool
+ * by the kernels and is NOT inserted; recency, counts, the trace and hits/misses are left untouched, so a one-off
+ * scan over a long prompt does not flush the cache.  Counted as stream_loads / bytes_streamed.
+ * Arguments as for moe_layer_decode; n_tokens <= max_batch.  Needs the tiled bf16 layout (MOE_ERR_UNSUPPORTED
+ * otherwise) and a device-visible pinned expert_pool.
+ */
+int moe_layer_prefill(moe_cache_t* cache, int32_t layer, const void* x_dev, const float* logit_bias_dev,
+                      int32_t n_tokens, void* y_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
 
 /* Counters of one layer (layer = -1: summed over layers).  Host-side, no device wait. */
 int moe_cache_stats(const moe_cache_t* cache, int32_t layer, moe_cache_stats_t* out);

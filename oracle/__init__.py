@@ -160,6 +160,7 @@ class ExpertCache:
         assert capacity >= 1 and n_experts >= 1
         self.E, self.C, self.policy, self.gamma = n_experts, capacity, policy, gamma
         self._h = C.c_void_p(lib().orc_cache_new(n_experts, capacity, policy, gamma))
+        self.stream_loads = 0     # experts streamed past the cache by prompt processing
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:
@@ -192,8 +193,10 @@ class ExpertCache:
     def stats(self, expert_bytes: int = 0) -> dict:
         out = np.zeros(6, dtype=np.uint64)
         lib().orc_cache_stats(self._h, out.ctypes.data_as(C.POINTER(C.c_uint64)), int(expert_bytes))
-        return dict(zip(("lookups", "hits", "misses", "evictions", "pin_loads", "bytes_h2d"),
-                        (int(v) for v in out)))
+        d = dict(zip(("lookups", "hits", "misses", "evictions", "pin_loads", "bytes_h2d"), (int(v) for v in out)))
+        d["stream_loads"] = self.stream_loads
+        d["bytes_streamed"] = self.stream_loads * int(expert_bytes)
+        return d
 
 
 # ----------------------------------------------------------- whole layer
@@ -246,6 +249,26 @@ def moe_layer_decode(weights: LayerWeights, cache: ExpertCache, x, bias, K: int,
             for (wg, wu, wd) in weights.shared:
                 y[b] += expert_swiglu(x[b], wg, wu, wd)
     return DecodeResult(y, idx, w, trace, logits, p)
+
+
+def moe_layer_prefill(weights: LayerWeights, cache: ExpertCache, x, bias, K: int, norm_topk: int = 1,
+                      rows=None) -> DecodeResult:
+    """Prompt tokens through one layer in streaming mode: Eq. 1-3 as in decode, but the cache is only read.
+    Selected experts that are not resident are counted as stream loads (once per call) and nothing is inserted.
+    rows: token rows whose output is evaluated (default all)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    B, d = x.shape
+    logits, p, idx, w = route(x, weights.router_w, bias, K, norm_topk)
+    resident = set(cache.resident())
+    cache.stream_loads += len(set(int(e) for e in idx.reshape(-1)) - resident)
+    y = np.zeros((B, d), dtype=np.float64)
+    for b in (range(B) if rows is None else rows):
+        for k in range(K):
+            wg, wu, wd = weights.expert(int(idx[b, k]))
+            y[b] += w[b, k] * expert_swiglu(x[b], wg, wu, wd)
+        for (wg, wu, wd) in weights.shared:
+            y[b] += expert_swiglu(x[b], wg, wu, wd)
+    return DecodeResult(y, idx, w, [], logits, p)
 
 
 def moe_layer_dense(weights: LayerWeights, n_experts: int, x, bias, K: int, norm_topk: int = 1):

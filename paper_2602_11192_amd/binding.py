@@ -29,7 +29,7 @@ MOE_LAYOUT_ROWMAJOR, MOE_LAYOUT_TILED = 0, 1
 MOE_FETCH_COPY_ENGINE, MOE_FETCH_IN_KERNEL = 0, 1
 
 EXPORTS = ["moe_expert_bytes", "moe_pack_expert", "moe_cache_create", "moe_cache_destroy", "moe_cache_reset",
-           "moe_cache_prefill_pins", "moe_layer_decode", "moe_cache_stats", "moe_cache_read_trace",
+           "moe_cache_prefill_pins", "moe_layer_decode", "moe_layer_prefill", "moe_cache_stats", "moe_cache_read_trace",
            "moe_cache_resident", "moe_cache_set_profiling", "moe_cache_timing", "moe_probe_stream",
            "moe_last_error", "moe_version"]
 
@@ -46,7 +46,8 @@ class moe_weights_t(C.Structure):
 
 
 class moe_cache_stats_t(C.Structure):
-    _fields_ = [(n, C.c_uint64) for n in ("lookups", "hits", "misses", "evictions", "pin_loads", "bytes_h2d")]
+    _fields_ = [(n, C.c_uint64) for n in ("lookups", "hits", "misses", "evictions", "pin_loads", "bytes_h2d",
+                                          "stream_loads", "bytes_streamed")]
 
 
 class moe_trace_rec_t(C.Structure):
@@ -82,6 +83,7 @@ def _load():
     lib.moe_cache_reset.argtypes = [vp, i32, i32, vp]
     lib.moe_cache_prefill_pins.argtypes = [vp, i32, C.POINTER(i32), i32, vp]
     lib.moe_layer_decode.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp]
+    lib.moe_layer_prefill.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp, vp]
     lib.moe_cache_stats.argtypes = [vp, i32, C.POINTER(moe_cache_stats_t)]
     lib.moe_cache_read_trace.argtypes = [vp, i32, C.POINTER(moe_trace_rec_t), i64, C.POINTER(i64), C.POINTER(i64)]
     lib.moe_cache_resident.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32)]
@@ -184,6 +186,11 @@ class MoECache:
         """x, y: device tensors [B, d] of the cache's dtype; logit_bias [B, E] fp32 or None."""
         _check(lib.moe_layer_decode(self._h, layer, _ptr(x), _ptr(logit_bias), x.shape[0], _ptr(y),
                                     _ptr(topk_idx), _ptr(topk_w), _stream(stream)))
+
+    def moe_layer_prefill(self, layer, x, y, logit_bias=None, topk_idx=None, topk_w=None, stream=None):
+        """Prompt tokens x [n, d] through one layer in streaming mode (the cache is read, never changed)."""
+        _check(lib.moe_layer_prefill(self._h, layer, _ptr(x), _ptr(logit_bias), x.shape[0], _ptr(y),
+                                     _ptr(topk_idx), _ptr(topk_w), _stream(stream)))
 
     def moe_cache_stats(self, layer=-1) -> dict:
         st = moe_cache_stats_t()

@@ -58,7 +58,10 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   const bool has_rows = rt < n_rt;
   const int rtc = has_rows ? rt : n_rt - 1;          // clamped: loads stay in bounds, results are dropped
 
-  const u32x4* w = reinterpret_cast<const u32x4*>(group_weights(a, gd.buf));
+  // a group whose expert is not resident streams it from the pinned host pool (prompt streaming)
+  const u32x4* w = (a.fetch != 0 && gd.miss != 0)
+                       ? reinterpret_cast<const u32x4*>(a.pool + (size_t)gd.expert * a.expert_bytes)
+                       : reinterpret_cast<const u32x4*>(group_weights(a, gd.buf));
   size_t kb_stride;
   if (NMAT == 2) {
     w += (size_t)rtc * nkb * 2 * 64 + lane;

@@ -334,7 +334,7 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->elem = cfg->dtype == MOE_DTYPE_FP32 ? 4 : 2;
   const int C = c->C, P = c->P, KS = c->KS, Bm = cfg->max_batch;
   const size_t NP = (size_t)Bm * KS;
-  c->G = (int)std::min<size_t>((size_t)Bm * K, (size_t)P) + cfg->n_shared;
+  c->G = (int)std::min<size_t>((size_t)Bm * K, (size_t)std::max(P, E)) + cfg->n_shared;   // buffers, or experts when streaming a prompt
   c->max_miss = (int)std::max<size_t>((size_t)Bm * K, (size_t)C);
   c->stats.assign(L, moe_cache_stats_t{});
 
@@ -424,16 +424,20 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->pin_ids = reinterpret_cast<int32_t*>(c->host_mem + align_up(sizeof(Mailbox), 64));
   c->miss_list = reinterpret_cast<MissEntry*>(c->host_mem + align_up(sizeof(Mailbox), 64) + align_up((size_t)C * 4, 64));
 
-  if (cfg->fetch_mode == MOE_FETCH_IN_KERNEL) {
+  {
+    // the pinned pool as the device sees it (in-kernel fetch, prompt streaming); absent for pageable memory
     void* dp = nullptr;
     hipError_t e_ = hipHostGetDevicePointer(&dp, const_cast<void*>(weights->expert_pool), 0);
-    if (e_ != hipSuccess || dp == nullptr) {
+    if (e_ == hipSuccess && dp != nullptr) {
+      c->pool_dev = static_cast<const char*>(dp);
+    } else {
       (void)hipGetLastError();
-      free_all(c);
-      return fail(MOE_ERR_UNSUPPORTED, "in-kernel fetch: expert_pool is not device-visible pinned host memory (%s)",
-                  hipGetErrorString(e_));
+      if (cfg->fetch_mode == MOE_FETCH_IN_KERNEL) {
+        free_all(c);
+        return fail(MOE_ERR_UNSUPPORTED, "in-kernel fetch: expert_pool is not device-visible pinned host memory (%s)",
+                    hipGetErrorString(e_));
+      }
     }
-    c->pool_dev = static_cast<const char*>(dp);
   }
   CREATE_CHK(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking), MOE_ERR_HIP);
   CREATE_CHK(hipEventCreateWithFlags(&c->ev_mail, hipEventDisableTiming), MOE_ERR_HIP);
@@ -614,6 +618,63 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   return MOE_OK;
 }
 
+int moe_layer_prefill(moe_cache_t* c, int32_t layer, const void* x_dev, const float* logit_bias_dev, int32_t n_tokens,
+                      void* y_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
+  if (!c) return fail(MOE_ERR_INVALID_ARG, "null cache");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  if (!x_dev || !y_dev) return fail(MOE_ERR_INVALID_ARG, "x_dev and y_dev must not be null");
+  if (n_tokens < 1 || n_tokens > c->cfg.max_batch)
+    return fail(MOE_ERR_INVALID_ARG, "n_tokens %d outside 1..max_batch=%d", n_tokens, c->cfg.max_batch);
+  if (reinterpret_cast<uintptr_t>(x_dev) & 15) return fail(MOE_ERR_INVALID_ARG, "x_dev must be 16-byte aligned");
+  if (c->cfg.pool_layout != MOE_LAYOUT_TILED) return fail(MOE_ERR_UNSUPPORTED, "prompt streaming needs the tiled bf16 layout");
+  if (!c->pool_dev) return fail(MOE_ERR_UNSUPPORTED, "prompt streaming: expert_pool is not device-visible pinned host memory");
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const moe_cache_config_t& cf = c->cfg;
+  const int E = cf.n_experts, K = cf.top_k, KS = c->KS, d = cf.d_model;
+
+  RouteArgs ra{};
+  ra.x = x_dev;
+  ra.router_w = static_cast<const char*>(c->w.router_w) + (size_t)layer * E * d * c->elem;
+  ra.bias = logit_bias_dev;
+  ra.d = d; ra.norm_topk = cf.norm_topk;
+  ra.user_idx = topk_idx_dev; ra.user_w = topk_w_dev;
+  ra.arrive = c->arrive;
+
+  CacheCallArgs a{};
+  a.mode = 2; a.B = n_tokens; a.K = K; a.KS = KS; a.E = E; a.C = c->C; a.P = c->P; a.n_shared = cf.n_shared;
+  a.policy = cf.policy; a.gamma = cf.gamma; a.trace_cap = 0; a.seq = ++c->seq;
+  a.pin_ids = nullptr; a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
+  HIPCHK(launch_route_cache(s, cf.dtype, ra, c->layers[layer], c->t, a, KernelEvents{}));
+  HIPCHK(hipEventRecord(c->ev_mail, s));
+
+  FfnArgs fa{};
+  fa.x = x_dev;
+  fa.buffers = c->buffers + (size_t)layer * c->P * c->expert_bytes;
+  fa.shared = cf.n_shared ? static_cast<const char*>(c->w.shared_w) + (size_t)layer * cf.n_shared * c->expert_bytes
+                          : nullptr;
+  fa.expert_bytes = c->expert_bytes;
+  fa.P = c->P; fa.d = d; fa.f = cf.d_ff; fa.KS = KS;
+  fa.g_max = (int)std::min<size_t>((size_t)n_tokens * K, (size_t)E) + cf.n_shared;   // groups are experts here
+  fa.max_count = n_tokens;
+  fa.t = c->t; fa.h = c->h; fa.o = c->o;
+  fa.pass = 2; fa.fused = 0;
+  fa.pool = c->pool_dev + (size_t)layer * E * c->expert_bytes;
+  fa.fetch = 1;
+  HIPCHK(launch_ffn_gemm(s, fa, KernelEvents{}, KernelEvents{}));
+
+  HIPCHK(hipEventSynchronize(c->ev_mail));
+  const uint32_t got = __atomic_load_n(&c->mailbox->seq, __ATOMIC_ACQUIRE);
+  if (got != a.seq) return fail(MOE_ERR_TIMEOUT, "group list of call %u not delivered (mailbox holds %u)", a.seq, got);
+  const Mailbox mb = *c->mailbox;
+  HIPCHK(launch_combine(s, cf.dtype, c->o, c->t.wpair, c->t.pos_of, n_tokens, KS, d, y_dev));
+  moe_cache_stats_t& st = c->stats[layer];
+  st.stream_loads += (uint64_t)mb.n_miss;
+  st.bytes_streamed += (uint64_t)mb.n_miss * c->expert_bytes;
+  return MOE_OK;
+}
+
 int moe_cache_stats(const moe_cache_t* c, int32_t layer, moe_cache_stats_t* out) {
   if (!c || !out) return fail(MOE_ERR_INVALID_ARG, "null argument");
   if (layer < -1 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
@@ -623,6 +684,7 @@ int moe_cache_stats(const moe_cache_t* c, int32_t layer, moe_cache_stats_t* out)
     const moe_cache_stats_t& v = c->stats[l];
     s.lookups += v.lookups; s.hits += v.hits; s.misses += v.misses;
     s.evictions += v.evictions; s.pin_loads += v.pin_loads; s.bytes_h2d += v.bytes_h2d;
+    s.stream_loads += v.stream_loads; s.bytes_streamed += v.bytes_streamed;
   }
   *out = s;
   return MOE_OK;

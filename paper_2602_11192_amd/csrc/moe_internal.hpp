@@ -63,7 +63,7 @@ struct CallTables {
 };
 
 struct CacheCallArgs {
-  int32_t mode;          // 0 decode, 1 pin
+  int32_t mode;          // 0 decode, 1 pin, 2 prompt streaming (cache read-only)
   int32_t B, K, KS, E, C, P, n_shared;
   int32_t policy;
   double gamma;

@@ -109,8 +109,9 @@ __host__ __device__ inline LdsLayout lds_layout(int E, int C, int P, int n_share
   l.used = o; o += (size_t)P * 4;
   l.filled = o; o += (size_t)P * 4;
   l.pending = o; o += (size_t)E * 4;
-  l.count = o; o += (size_t)(P + n_shared) * 4;
-  l.start = o; o += (size_t)(P + n_shared) * 4;
+  const int n_keys = (P > E ? P : E) + n_shared;     // grouping keys: buffer ids, or expert ids when streaming a prompt
+  l.count = o; o += (size_t)n_keys * 4;
+  l.start = o; o += (size_t)n_keys * 4;
   l.logit = o; o += (size_t)E * 4;
   const bool stage = stage_in_lds(B, KS);
   l.idx_stage = o; o += stage ? (size_t)B * K * 4 : 0;
@@ -259,6 +260,79 @@ __device__ int group_pairs_lds(int32_t* count, int32_t* cursor, const int32_t* f
   wave_sync();
   for (int gi = lane; gi < n_groups; gi += kWave) t.grp[gi].pair0 = t.sorted_pair[t.grp[gi].begin];
   return n_groups;
+}
+
+// ---------------------------------------------------------------- prompt streaming
+// Phase 3 of a prefill call: the cache is only READ.  Pairs are grouped by expert; a group whose expert is
+// resident reads its buffer, any other group streams its expert from the pinned host pool (miss = 1) and
+// nothing is inserted or refreshed, so a one-off scan over a long prompt leaves the cache as the prefetch set
+// it.  Runs in ONE wave; idx [B][K] routed experts (LDS or global), keys [B*KS] scratch.
+__device__ void prefill_phase(unsigned char* smem, const LdsLayout& L, const int32_t* idx, int32_t* keys,
+                              const LayerState& st, const CallTables& t, const CacheCallArgs& a) {
+  int32_t* slot_of = reinterpret_cast<int32_t*>(smem + L.slot_of);
+  int32_t* count = reinterpret_cast<int32_t*>(smem + L.count);
+  int32_t* cursor = reinterpret_cast<int32_t*>(smem + L.start);
+  const int lane = threadIdx.x & 63;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const int E = a.E, C = a.C, K = a.K, KS = a.KS, P = a.P;
+  const int NP = a.B * KS, NB = E + a.n_shared;
+  for (int e = lane; e < E; e += kWave) slot_of[e] = -1;
+  for (int i = lane; i < NB; i += kWave) count[i] = 0;
+  wave_sync();
+  for (int s = lane; s < C; s += kWave) {
+    const int ex = st.expert_in[s];
+    if (ex >= 0) slot_of[ex] = st.buf_of_slot[s];          // expert -> the buffer that holds it
+  }
+  for (int p = lane; p < NP; p += kWave) {
+    const int b = p / KS, k = p - b * KS;
+    keys[p] = k < K ? idx[(size_t)b * K + k] : E + (k - K);
+  }
+  wave_sync();
+  for (int p = lane; p < NP; p += kWave) atomicAdd(&count[keys[p]], 1);
+  wave_sync();
+  int n_groups = 0, offset = 0, n_stream = 0;
+  for (int base = 0; base < NB; base += kWave) {
+    const int id = base + lane;
+    const int c = id < NB ? count[id] : 0;
+    int incl = c;
+#pragma unroll
+    for (int dlt = 1; dlt < kWave; dlt <<= 1) {
+      const int v = __shfl_up(incl, dlt);
+      if (lane >= dlt) incl += v;
+    }
+    const int begin = offset + incl - c;
+    const uint64_t gm = __ballot(c > 0);
+    const int buf = id < E ? slot_of[id < E ? id : 0] : P + (id - E);
+    const bool streamed = c > 0 && id < E && buf < 0;
+    if (c > 0) {
+      GroupDesc gd;
+      gd.buf = streamed ? 0 : buf; gd.begin = begin; gd.count = c; gd.miss = streamed ? 1 : 0;
+      gd.pair0 = 0; gd.expert = streamed ? id : -1; gd.pad[0] = gd.pad[1] = 0;
+      t.grp[n_groups + __popcll(gm & lt_mask)] = gd;
+    }
+    if (id < NB) cursor[id] = begin;
+    n_groups += __popcll(gm);
+    n_stream += __popcll(__ballot(streamed));
+    offset += __shfl(incl, kWave - 1);
+  }
+  wave_sync();
+  for (int p = lane; p < NP; p += kWave) {
+    const int pos = atomicAdd(&cursor[keys[p]], 1);
+    t.sorted_pair[pos] = p;
+    t.pos_of[p] = pos;
+  }
+  wave_sync();
+  for (int gi = lane; gi < n_groups; gi += kWave) t.grp[gi].pair0 = t.sorted_pair[t.grp[gi].begin];
+  if (lane == 0) {
+    *t.n_groups = n_groups;
+    Mailbox* mb = a.mailbox;
+    mb->status = MOE_OK;
+    mb->n_miss = n_stream;
+    mb->n_evict = 0;
+    mb->n_groups = n_groups;
+    mb->n_hits = 0;
+    mb->seq = a.seq;
+  }
 }
 
 // ---------------------------------------------------------------- phase 3
@@ -720,7 +794,7 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
   const int b = blockIdx.x;
   const int E = a.E, K = a.K, KS = a.KS, d = r.d;
   const bool single = gridDim.x == 1;
-  const bool fast = fast_table(a.policy, a.C, a.P, a.n_shared);
+  const bool fast = a.mode != 2 && fast_table(a.policy, a.C, a.P, a.n_shared);
   PHASE_TS(0);
 
   // With one workgroup the cache table can be fetched while the router GEMV runs.
@@ -805,7 +879,9 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
   PHASE_TS(3);
 
   // ---- phase 3: cache lookups, one wave ----
-  if (fast) {
+  if (a.mode == 2) {
+    prefill_phase(smem, L, stage ? idx_stage : t.idx, pair_stage, st, t, a);
+  } else if (fast) {
     cache_phase_fast(ft, smem, L, stage ? idx_stage : t.idx, pair_stage, st, t, a);
   } else {
     cache_phase_general(smem, L, stage ? idx_stage : t.idx, pair_stage, st, t, a);

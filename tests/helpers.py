@@ -36,6 +36,10 @@ class OracleStack:
         return oracle.moe_layer_decode(lw, self.caches[l], x32, bias, self.cfg.top_k,
                                        self.cfg.norm_topk if norm_topk is None else norm_topk, compute_y)
 
+    def prefill(self, l, x32, bias, rows=None):
+        lw = oracle.LayerWeights(self.router[l], lambda e: self.expert(l, e), self.shared[l])
+        return oracle.moe_layer_prefill(lw, self.caches[l], x32, bias, self.cfg.top_k, self.cfg.norm_topk, rows)
+
 
 def rel_err(y, ref):
     """Per token: max_i |y_i - ref_i| / max_i |ref_i|."""

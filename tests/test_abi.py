@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(B):
 
 def test_struct_sizes_match_header(B):
     assert C.sizeof(B.moe_cache_config_t) == 16 * 4 + 8
-    assert C.sizeof(B.moe_cache_stats_t) == 48
+    assert C.sizeof(B.moe_cache_stats_t) == 64
     assert C.sizeof(B.moe_trace_rec_t) == 16
     assert C.sizeof(B.moe_weights_t) == 24
 

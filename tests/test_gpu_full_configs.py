@@ -144,3 +144,50 @@ def test_deepseek_like_batched_shared_cache(torch, P):
         trace += res.trace
     compare_traces_and_stats(cache, ost, [trace], cfg.expert_bytes)
     cache.close()
+
+
+def test_deepseek_like_prompt_then_decode(torch, P):
+    """A 512-token prompt streams through the layer (grouped GEMM, missing experts read from the host pool);
+    the prefetch set is the Top-C of the mean router probability over the prompt - the activation predictor's
+    own training target (section 3.1.2) standing in for the predictor; then the sequence decodes."""
+    cfg = get_config("deepseek_like").with_(n_layers=1, n_seqs=1, n_steps=16)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, max_batch=cfg.prefill_len, trace_capacity=4096)
+    ost = OracleStack(wl, keep=cfg.n_experts)
+    xs = wl.prefill_tokens(0)
+    n = xs.shape[0]
+    bias = np.tile(wl.bias(0, 0), (n, 1))
+    y = torch.empty((n, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.empty((n, cfg.top_k), dtype=torch.int32, device="cuda:0")
+    cache.moe_layer_prefill(0, P.to_device(xs), y, torch.from_numpy(bias).cuda(), idx)
+    rows = list(range(0, n, 37))
+    res = ost.prefill(0, widen(xs), bias, rows=rows)
+    torch.cuda.synchronize()
+    assert idx.cpu().numpy().tolist() == res.idx.tolist()
+    assert rel_err(P.to_numpy(y)[rows], res.y[rows]).max() <= TOL["bf16"]
+    st = cache.moe_cache_stats(0)
+    assert st["stream_loads"] == ost.caches[0].stream_loads == len(set(res.idx.reshape(-1).tolist()))
+    assert st["lookups"] == 0 and cache.moe_cache_resident(0) == []
+    # prefetch set from the prompt's mean router probability, best expert loaded last
+    score = res.p.mean(axis=0)
+    pins = np.argsort(score, kind="stable")[-cfg.capacity:].astype(np.int32)
+    cache.moe_cache_prefill_pins(0, pins)
+    ost.caches[0].pin(pins)
+    trace = []
+    yd = torch.empty((1, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    idd = torch.empty((1, cfg.top_k), dtype=torch.int32, device="cuda:0")
+    toks = wl.tokens(0)
+    b1 = wl.bias(0, 0)[None, :]
+    b1_dev = torch.from_numpy(b1).cuda()
+    for t in range(cfg.n_steps):
+        cache.moe_layer_decode(0, P.to_device(toks[t:t + 1]), yd, b1_dev, idd)
+        r = ost.decode(0, widen(toks[t:t + 1]), b1, compute_y=t % 4 == 0)
+        torch.cuda.synchronize()
+        assert idd.cpu().numpy().tolist() == r.idx.tolist()
+        if t % 4 == 0:
+            assert rel_err(P.to_numpy(yd), r.y).max() <= TOL["bf16"]
+        trace += r.trace
+    compare_traces_and_stats(cache, ost, [trace], cfg.expert_bytes)
+    st = cache.moe_cache_stats(0)
+    print("deepseek_like prompt+decode: streamed %d experts, decode hit rate %.3f" % (st["stream_loads"], st["hits"] / st["lookups"]))
+    cache.close()

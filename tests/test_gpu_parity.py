@@ -217,6 +217,36 @@ def test_many_tokens_per_expert_take_the_grouped_gemm(torch, P, n_experts, top_k
     cache.close()
 
 
+@pytest.mark.parametrize("n_tokens", [1, 40, 200])
+def test_prompt_streaming_reads_the_cache_without_changing_it(torch, P, n_tokens):
+    cfg = small_cfg(n_seqs=3, n_steps=8, n_layers=1, capacity=6, n_shared=1, prefill_len=n_tokens, d_model=160)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=max(n_tokens, 2), trace_capacity=4096)
+    ost = OracleStack(wl)
+    pins = wl.prefetch_list(0, 0)[:4]
+    cache.moe_cache_prefill_pins(0, pins)
+    ost.caches[0].pin(pins)
+    xs = wl.prefill_tokens(0)
+    bias = np.tile(wl.bias(0, 0), (n_tokens, 1))
+    y = torch.empty((n_tokens, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.empty((n_tokens, cfg.top_k), dtype=torch.int32, device="cuda:0")
+    gw = torch.empty((n_tokens, cfg.top_k), dtype=torch.float32, device="cuda:0")
+    for _ in range(2):                                   # twice: the second call must see the same cache
+        cache.moe_layer_prefill(0, P.to_device(xs), y, torch.from_numpy(bias).cuda(), idx, gw)
+        res = ost.prefill(0, widen(xs), bias)
+        torch.cuda.synchronize()
+        assert idx.cpu().numpy().tolist() == res.idx.tolist()
+        np.testing.assert_allclose(gw.cpu().numpy(), res.w, rtol=0, atol=2e-5)
+        assert rel_err(P.to_numpy(y), res.y).max() <= TOL["bf16"]
+    assert ost.caches[0].stream_loads > 0 or n_tokens == 1
+    # the cache is as the pins left it, and decoding afterwards follows the oracle's trace
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, [0], step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_staging_exhausted_leaves_cache_unchanged(torch, P):
     from paper_2602_11192_amd import binding as B
     cfg = small_cfg(n_seqs=8, n_steps=4, n_layers=1, capacity=4, pref_lo=0, pref_hi=0, beta=0.0)

@@ -221,6 +221,7 @@ def test_pins_are_loads_not_lookups_and_order_sets_recency():
     c.pin([5, 2, 7])
     st = c.stats(10)
     assert (st["lookups"], st["hits"], st["misses"], st["pin_loads"], st["bytes_h2d"]) == (0, 0, 0, 3, 30)
+    assert (st["stream_loads"], st["bytes_streamed"]) == (0, 0)
     assert set(c.resident()) == {2, 5, 7}
     assert c.lookup(2) == (True, -1)
     assert c.lookup(0) == (False, 5)          # first listed = least recent

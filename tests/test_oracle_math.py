@@ -211,6 +211,29 @@ def test_layer_with_k_equal_e_is_full_mixture_and_shared_adds():
         np.testing.assert_allclose(res2.y[b] - res.y[b], oracle.expert_swiglu(x[b], *ex[E]), atol=1e-12)
 
 
+def test_prefill_streaming_is_the_same_layer_with_a_read_only_cache():
+    cfg = get_config("tiny_fp32")
+    wl = Workload(cfg)
+    experts = [tuple(widen(m) for m in wl.expert(0, e)) for e in range(cfg.n_experts)]
+    lw = oracle.LayerWeights(widen(wl.router_w(0)), lambda e: experts[e])
+    x = widen(wl.tokens(0))[:6]
+    bias = np.tile(wl.bias(0, 0), (6, 1))
+    cache = oracle.ExpertCache(cfg.n_experts, 3)
+    cache.pin([1, 4, 6])
+    before = (cache.resident(), cache.stats(8))
+    res = oracle.moe_layer_prefill(lw, cache, x, bias, cfg.top_k)
+    np.testing.assert_array_equal(res.y, oracle.moe_layer_dense(lw, cfg.n_experts, x, bias, cfg.top_k))
+    assert cache.resident() == before[0]                       # nothing inserted, nothing evicted
+    used = set(res.idx.reshape(-1).tolist())
+    st = cache.stats(8)
+    assert st["stream_loads"] == len(used - {1, 4, 6}) and st["bytes_streamed"] == 8 * st["stream_loads"]
+    assert {k: st[k] for k in before[1] if "stream" not in k} == {k: v for k, v in before[1].items() if "stream" not in k}
+    # rows=... evaluates a subset only
+    sub = oracle.moe_layer_prefill(lw, cache, x, bias, cfg.top_k, rows=[2, 5])
+    np.testing.assert_array_equal(sub.y[[2, 5]], res.y[[2, 5]])
+    assert not sub.y[[0, 1, 3, 4]].any()
+
+
 # ------------------------------------------------------------- byte model
 def test_expert_bytes_against_paper_transfer_time():
     k = paper_constants()

@@ -249,6 +249,31 @@ int moe_cache_timing(moe_cache_t* cache, moe_timing_t* out, int32_t clear);
 int moe_probe_stream(void* src_dev, void* dst_dev, uint64_t bytes, int32_t mode, int32_t iters,
                      void* hip_stream, double* avg_ms);
 
+/*
+ * Cache-simulation loss, forward value (paper section 3.1.1; appendix C.1, Definition C.1 and
+ * Proposition C.2).  Not part of the decode path: it scores routing traces, e.g. the idx output of
+ * moe_layer_decode collected over a sequence, by how cache-friendly they are.
+ *
+ * idx_dev   device, int32 [n_traces][T][K]: the K distinct experts requested at each token (the request
+ *           vector r^(t), ||r||_1 = K), one trace per (sequence, layer); may be NULL when it holds no element.
+ * c1_dev    device, fp64 [n_traces][n_experts]: first cache state c^(1), L1 norm = capacity (for instance
+ *           the indicator of a prefetch set); NULL = uniform capacity/n_experts.
+ * out_dev   device, fp64 [n_traces][2]: per trace
+ *             [0] sum_t <r^(t), 1 - c^(t)> with the soft cache  Gamma^(1) = 1,
+ *                 c^(t+1) = (gamma Gamma^(t) c^(t) + r^(t)) / Gamma^(t+1),  Gamma^(t+1) = gamma Gamma^(t) + K/capacity;
+ *             [1] sum_t <r^(t), 1 - Chat^(t)>, Chat^(t) = Top-capacity of the discounted counts
+ *                 Ctilde^(t+1) = gamma Ctilde^(t) + r^(t), Ctilde^(1) = c^(1), ties to the lower expert id.
+ *           L_cs and L_cs^hard are these sums added over the traces and divided by n_traces * T.
+ * flag_dev  device, int32 [n_traces]: 0, or 1 if the trace held an id outside 0..n_experts-1 (its sums then
+ *           stop at that token).
+ * All arithmetic is fp64 in the order written above.  The kernel is enqueued on hip_stream; the call does not
+ * wait for it.  Limits: n_experts <= 1024, K <= 64, 0 <= gamma <= 1; violations return MOE_ERR_INVALID_ARG.
+ * The library keeps no reference to any argument.
+ */
+int moe_cache_sim_loss(const int32_t* idx_dev, int32_t n_traces, int32_t T, int32_t K, int32_t n_experts,
+                       int32_t capacity, double gamma, const double* c1_dev, double* out_dev, int32_t* flag_dev,
+                       void* hip_stream);
+
 /* Text of the last error on this thread ("" if none). */
 const char* moe_last_error(void);
 

@@ -65,6 +65,7 @@ def lib():
         l.orc_cache_resident.argtypes = [C.c_void_p, i32p]
         l.orc_cache_resident.restype = C.c_int
         l.orc_cache_stats.argtypes = [C.c_void_p, u64p, C.c_uint64]
+        l.orc_cache_sim_loss.argtypes = [i32p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, f64p, f64p, f64p]
         _lib = l
     return _lib
 
@@ -291,6 +292,27 @@ def moe_layer_dense(weights: LayerWeights, n_experts: int, x, bias, K: int, norm
         for (wg, wu, wd) in weights.shared:
             y[b] += expert_swiglu(x[b], wg, wu, wd)
     return y
+
+
+def cache_sim_loss(idx, n_experts: int, capacity: int, gamma: float, c1=None):
+    """Forward value of the cache-simulation loss of section 3.1.1 / appendix C.1 over a routing trace.
+    idx [L][T][K] selected experts.  Returns (L_cs, L_cs_hard): the soft loss with the soft cache of
+    Proposition C.2 and the hard miss count of Definition C.1 (Top-C ties to the lower id), both divided by
+    L*T.  c1 [L][E] is the first cache state (L1 norm C); None = uniform C/E."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    L, T, K = idx.shape
+    soft_sum = hard_sum = 0.0
+    for l in range(L):
+        row = np.ascontiguousarray(idx[l])
+        c1p = None
+        if c1 is not None:
+            c1l, c1p = _f64(np.asarray(c1)[l])
+        so, ho = C.c_double(), C.c_double()
+        lib().orc_cache_sim_loss(row.ctypes.data_as(C.POINTER(C.c_int32)), T, K, int(n_experts), int(capacity),
+                                 float(gamma), c1p, C.byref(so), C.byref(ho))
+        soft_sum += so.value
+        hard_sum += ho.value
+    return soft_sum / (L * T), hard_sum / (L * T)
 
 
 def expert_bytes(d: int, f: int, elem_bytes: int) -> int:

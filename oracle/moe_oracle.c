@@ -242,3 +242,48 @@ void orc_cache_stats(const orc_cache_t* c, uint64_t* out6, uint64_t expert_bytes
   out6[0] = c->lookups; out6[1] = c->hits; out6[2] = c->misses; out6[3] = c->evictions;
   out6[4] = c->pin_loads; out6[5] = (c->misses + c->pin_loads) * expert_bytes;
 }
+
+/* ---- cache-simulation loss (section 3.1.1; appendix C.1, Proposition C.2) ----------------
+ * Forward value of L_cs and of the hard miss count L_cs^hard for ONE layer over a routing trace
+ * idx[T][K] (the request vectors r^(t), ||r||_1 = K).
+ *
+ * Soft cache (Proposition C.2): Gamma^(1) = 1,
+ *     c^(t+1) = (gamma Gamma^(t) c^(t) + r^(t)) / Gamma^(t+1),   Gamma^(t+1) = gamma Gamma^(t) + K/C,
+ * started from c1[E] with ||c1||_1 = C (uniform C/E when c1 is NULL: the initialisation that skips the
+ * fill phase).  soft = sum_t <r^(t), 1 - c^(t)>.
+ *
+ * Hard cache (Definition C.1): Ctilde^(t+1) = gamma Ctilde^(t) + r^(t), Chat = Top-C(Ctilde) with ties to
+ * the lower id, started from Ctilde^(1) = c1.  hard = sum_t <r^(t), 1 - Chat^(t)>.
+ * The caller divides by L*T.
+ */
+void orc_cache_sim_loss(const int32_t* idx, int T, int K, int E, int C, double gamma, const double* c1,
+                        double* soft_out, double* hard_out) {
+  double* c = (double*)malloc((size_t)E * sizeof(double));
+  double* ct = (double*)malloc((size_t)E * sizeof(double));
+  char* in_top = (char*)malloc((size_t)E);
+  for (int e = 0; e < E; ++e) { c[e] = c1 ? c1[e] : (double)C / (double)E; ct[e] = c[e]; }
+  double Gamma = 1.0, soft = 0.0, hard = 0.0;
+  for (int t = 0; t < T; ++t) {
+    const int32_t* r = idx + (size_t)t * K;
+    /* Top-C of the discounted counts */
+    memset(in_top, 0, (size_t)E);
+    for (int j = 0; j < C && j < E; ++j) {
+      int best = -1;
+      for (int e = 0; e < E; ++e)
+        if (!in_top[e] && (best < 0 || ct[e] > ct[best])) best = e;
+      in_top[best] = 1;
+    }
+    for (int k = 0; k < K; ++k) {
+      soft += 1.0 - c[r[k]];
+      hard += in_top[r[k]] ? 0.0 : 1.0;
+    }
+    const double Gamma_next = gamma * Gamma + (double)K / (double)C;
+    for (int e = 0; e < E; ++e) { c[e] = gamma * Gamma * c[e]; ct[e] = gamma * ct[e]; }
+    for (int k = 0; k < K; ++k) { c[r[k]] += 1.0; ct[r[k]] += 1.0; }
+    for (int e = 0; e < E; ++e) c[e] = c[e] / Gamma_next;
+    Gamma = Gamma_next;
+  }
+  *soft_out = soft;
+  *hard_out = hard;
+  free(c); free(ct); free(in_top);
+}

@@ -31,7 +31,7 @@ MOE_FETCH_COPY_ENGINE, MOE_FETCH_IN_KERNEL = 0, 1
 EXPORTS = ["moe_expert_bytes", "moe_pack_expert", "moe_cache_create", "moe_cache_destroy", "moe_cache_reset",
            "moe_cache_prefill_pins", "moe_layer_decode", "moe_layer_prefill", "moe_cache_stats", "moe_cache_read_trace",
            "moe_cache_resident", "moe_cache_set_profiling", "moe_cache_timing", "moe_probe_stream",
-           "moe_last_error", "moe_version"]
+           "moe_cache_sim_loss", "moe_last_error", "moe_version"]
 
 
 class moe_cache_config_t(C.Structure):
@@ -90,6 +90,7 @@ def _load():
     lib.moe_cache_set_profiling.argtypes = [vp, i32]
     lib.moe_cache_timing.argtypes = [vp, C.POINTER(moe_timing_t), i32]
     lib.moe_probe_stream.argtypes = [vp, vp, C.c_uint64, i32, i32, vp, C.POINTER(C.c_double)]
+    lib.moe_cache_sim_loss.argtypes = [vp, i32, i32, i32, i32, i32, C.c_double, vp, vp, vp, vp]
     lib.moe_last_error.restype = C.c_char_p
     lib.moe_version.restype = C.c_char_p
     for name in EXPORTS:
@@ -132,6 +133,24 @@ def moe_probe_stream(src, dst, nbytes: int, mode: int, iters: int = 10, stream=N
     if rc != MOE_OK:
         raise MoeError(rc, "moe_probe_stream failed")
     return ms.value
+
+
+def moe_cache_sim_loss(idx, n_experts: int, capacity: int, gamma: float, c1=None, out=None, flag=None, stream=None):
+    """Per-trace sums of the soft cache-simulation loss and of the hard miss count for device tensor
+    idx [n_traces][T][K] (int32).  Returns (out [n_traces][2] fp64, flag [n_traces] int32) device tensors."""
+    import torch
+    assert idx.dtype == torch.int32 and idx.dim() == 3 and idx.is_contiguous() and idx.is_cuda
+    n, T, K = idx.shape
+    if out is None:
+        out = torch.empty((n, 2), dtype=torch.float64, device=idx.device)
+    if flag is None:
+        flag = torch.empty((n,), dtype=torch.int32, device=idx.device)
+    if c1 is not None:
+        assert c1.dtype == torch.float64 and tuple(c1.shape) == (n, n_experts) and c1.is_contiguous()
+    assert out.dtype == torch.float64 and out.numel() == 2 * n and flag.dtype == torch.int32 and flag.numel() == n
+    _check(lib.moe_cache_sim_loss(_ptr(idx), n, T, K, n_experts, capacity, float(gamma), _ptr(c1), _ptr(out),
+                                  _ptr(flag), _stream(stream)))
+    return out, flag
 
 
 def _ptr(t):

@@ -25,9 +25,10 @@
 using namespace moe;
 
 namespace {
-
 thread_local char g_err[512] = "";
+}
 
+namespace moe {
 int fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -35,6 +36,9 @@ int fail(int code, const char* fmt, ...) {
   va_end(ap);
   return code;
 }
+}  // namespace moe
+
+namespace {
 
 #define HIPCHK(expr)                                                                        \
   do {                                                                                      \

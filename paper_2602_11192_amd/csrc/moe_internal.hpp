@@ -138,4 +138,7 @@ inline void launch_timed(void (*kernel)(Args...), dim3 grid, dim3 block, size_t 
     hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
 }
 
+// Records the text returned by moe_last_error() on this thread and returns `code`.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
 }  // namespace moe

@@ -295,3 +295,51 @@ def test_error_paths_on_device(torch, P):
             call()
         assert ei.value.code == B.MOE_ERR_INVALID_ARG
     cache.close()
+
+
+# ------------------------------------------------------------- cache-simulation loss (section 3.1.1, appendix C.1)
+@pytest.mark.gpu
+@pytest.mark.parametrize("E,K,C,T,gamma,init", [
+    (64, 8, 16, 300, 0.9, "uniform"), (8, 2, 5, 257, 1.0, "uniform"), (16, 2, 10, 200, 0.0, "prefetch"),
+    (1000, 6, 100, 120, 0.5, "uniform"), (64, 6, 12, 64, 0.97, "prefetch"), (5, 1, 1, 33, 0.3, "uniform"),
+    (130, 64, 65, 40, 0.8, "prefetch")])
+def test_cache_sim_loss_matches_oracle(torch, E, K, C, T, gamma, init):
+    from paper_2602_11192_amd import binding as B
+    n = 5
+    r = np.random.default_rng(E * 1000 + K)
+    w = 1.0 / np.arange(1, E + 1) ** 0.8
+    w /= w.sum()
+    idx = np.array([[np.sort(r.choice(E, size=K, replace=False, p=w)) for _ in range(T)] for _ in range(n)],
+                   dtype=np.int32)
+    c1 = None
+    if init == "prefetch":
+        c1 = np.zeros((n, E))
+        for i in range(n):
+            c1[i, r.choice(E, size=C, replace=False)] = 1.0
+    out, flag = B.moe_cache_sim_loss(torch.from_numpy(idx).cuda(), E, C, gamma,
+                                     None if c1 is None else torch.from_numpy(c1).cuda())
+    torch.cuda.synchronize()
+    out = out.cpu().numpy()
+    assert flag.cpu().numpy().tolist() == [0] * n
+    for i in range(n):
+        soft, hard = oracle.cache_sim_loss(idx[i:i + 1], E, C, gamma, None if c1 is None else c1[i:i + 1])
+        assert out[i, 1] == round(hard * T)                       # miss count: exact
+        assert out[i, 0] == pytest.approx(soft * T, rel=1e-12, abs=1e-12)
+
+
+@pytest.mark.gpu
+def test_cache_sim_loss_edges(torch):
+    from paper_2602_11192_amd import binding as B
+    idx = torch.zeros((2, 0, 2), dtype=torch.int32, device="cuda")            # no tokens
+    out, flag = B.moe_cache_sim_loss(idx, 8, 4, 0.9)
+    torch.cuda.synchronize()
+    assert out.cpu().numpy().tolist() == [[0.0, 0.0], [0.0, 0.0]] and flag.cpu().tolist() == [0, 0]
+    bad = torch.tensor([[[0, 1], [1, 9]], [[2, 3], [4, 5]]], dtype=torch.int32, device="cuda")
+    out, flag = B.moe_cache_sim_loss(bad, 8, 4, 0.9)                           # id 9 is outside 0..7
+    torch.cuda.synchronize()
+    assert flag.cpu().tolist() == [1, 0]
+    for args in [(0, 4, 0.9), (8, 0, 0.9), (8, 9, 0.9), (8, 4, 1.5), (2000, 4, 0.9)]:
+        with pytest.raises(B.MoeError):
+            B.moe_cache_sim_loss(bad, *args)
+    with pytest.raises(B.MoeError):
+        B.moe_cache_sim_loss(torch.zeros((1, 2, 9), dtype=torch.int32, device="cuda"), 8, 4, 0.9)   # K > E

@@ -52,11 +52,11 @@ typedef enum {
 
 enum { MOE_DTYPE_FP32 = 0, MOE_DTYPE_BF16 = 1 };
 enum { MOE_POLICY_LRU = 0, MOE_POLICY_GAMMA = 1 };
-enum { MOE_LAYOUT_ROWMAJOR = 0, MOE_LAYOUT_TILED = 1 };
+enum { MOE_LAYOUT_ROWMAJOR = 0, MOE_LAYOUT_TILED = 1, MOE_LAYOUT_TILED_INT4 = 2 };
 /*
  * MOE_FETCH_COPY_ENGINE  hipMemcpyAsync from the pinned pool on the library's copy stream, ordered by events
  *                        before the FFN pass over the fetched experts; the FFN over resident experts overlaps it.
- * MOE_FETCH_IN_KERNEL    decode calls of up to 16 tokens on the tiled bf16 layout: the expert kernel itself reads a
+ * MOE_FETCH_IN_KERNEL    decode calls of up to 16 tokens on a tiled layout (bf16 or INT4): the expert kernel itself reads a
  *                        missed expert from the pinned pool over PCIe while it computes, and fills the device
  *                        buffer on the way; no copy engine and no host round trip on the miss path.  Calls the
  *                        single-launch kernel does not cover, and prefill_pins, use the copy engine.
@@ -99,10 +99,19 @@ typedef struct {
  * Parameters.  All BORROWED for the life of the cache.
  *
  * An expert block holds the three matrices of Eq. 3 for one expert,
- * expert_bytes = 3 * d * d_ff * sizeof(dtype) bytes:
- *   MOE_LAYOUT_ROWMAJOR  W_g [d_ff][d] | W_u [d_ff][d] | W_d [d][d_ff], row-major.
- *   MOE_LAYOUT_TILED     bf16 only; the same values permuted into the order the
- *                        streaming kernels read them (written by moe_pack_expert).
+ * moe_expert_block_bytes() bytes (3 * d * d_ff * sizeof(dtype) for the first two layouts):
+ *   MOE_LAYOUT_ROWMAJOR    W_g [d_ff][d] | W_u [d_ff][d] | W_d [d][d_ff], row-major.
+ *   MOE_LAYOUT_TILED       bf16 only; the same values permuted into the order the
+ *                          streaming kernels read them (written by moe_pack_expert).
+ *   MOE_LAYOUT_TILED_INT4  4-bit group-quantised experts (section 3.2: experts are held in
+ *                          INT4 so that more of them stay resident): every run of 32
+ *                          consecutive elements along a matrix's contraction dimension
+ *                          (d for W_g, W_u; d_ff for W_d) is stored as 32 codes q in 0..15
+ *                          and one bf16 scale s and stands for the weights s * (q - 8);
+ *                          4.5 bits per weight.  Written by moe_pack_expert_int4.  x, y and
+ *                          the router stay bf16 (dtype = MOE_DTYPE_BF16); decode calls only
+ *                          (max_batch <= 16, no moe_layer_prefill); needs d % 256 == 0,
+ *                          d_ff % 32 == 0.  Statistics count bytes of this block size.
  */
 typedef struct {
   const void* router_w;    /* device, [L][E][d] row-major, dtype                            */
@@ -149,12 +158,27 @@ typedef struct {
 /* Bytes of one expert block for the given shape; 0 if the arguments are invalid. */
 uint64_t moe_expert_bytes(int32_t d_model, int32_t d_ff, int32_t dtype);
 
+/* Bytes of one expert block in the given layout (MOE_LAYOUT_*); 0 if the arguments are invalid. */
+uint64_t moe_expert_block_bytes(int32_t d_model, int32_t d_ff, int32_t dtype, int32_t pool_layout);
+
 /*
  * Host-side helper: permute one bf16 expert from MOE_LAYOUT_ROWMAJOR (src, host)
  * into MOE_LAYOUT_TILED (dst, host; may be pinned).  Pure data movement.
  * Requires d_model % 32 == 0 and d_ff % 32 == 0.  src and dst must not overlap.
  */
 int moe_pack_expert(const void* src_rowmajor, void* dst_tiled, int32_t d_model, int32_t d_ff);
+
+/*
+ * Host-side helper: write one MOE_LAYOUT_TILED_INT4 block (dst_block, host; may be pinned;
+ * moe_expert_block_bytes() bytes) from an already quantised expert.  Pure data movement: the
+ * quantiser is the caller's.
+ *   codes   host, 3 * d * d_ff bytes, one code 0..15 per byte: W_g [d_ff][d] | W_u [d_ff][d] | W_d [d][d_ff]
+ *   scales  host, bf16 bits, 3 * d * d_ff / 32 values: S_g [d_ff][d/32] | S_u [d_ff][d/32] | S_d [d][d_ff/32];
+ *           element [r][g] scales columns 32 g .. 32 g + 31 of row r
+ * Requires d_model % 128 == 0 and d_ff % 32 == 0; a code above 15 is MOE_ERR_INVALID_ARG.
+ */
+int moe_pack_expert_int4(const uint8_t* codes, const uint16_t* scales, void* dst_block, int32_t d_model,
+                         int32_t d_ff);
 
 /*
  * Create a cache for a layer stack: allocates L * (C + staging_buffers) expert

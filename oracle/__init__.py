@@ -315,6 +315,24 @@ def cache_sim_loss(idx, n_experts: int, capacity: int, gamma: float, c1=None):
     return soft_sum / (L * T), hard_sum / (L * T)
 
 
+def dequant_int4(codes, scale_bits) -> np.ndarray:
+    """4-bit group-quantised matrix -> its weights (section 3.2 keeps experts in INT4; the format here is the
+    generic symmetric one: 32 consecutive elements of a row share one bf16 scale, weight = scale * (code - 8)).
+    codes [rows][k] integers 0..15, scale_bits [rows][k/32] bf16 bit patterns.  Exact in float32 (8 x 4 bits)."""
+    codes = np.asarray(codes)
+    scale = (np.asarray(scale_bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    rows, k = codes.shape
+    assert scale.shape == (rows, k // 32) and k % 32 == 0
+    grouped = codes.astype(np.float64).reshape(rows, k // 32, 32)            # [row][group][element of the group]
+    out = scale.astype(np.float64)[:, :, None] * (grouped - 8.0)
+    return out.reshape(rows, k).astype(np.float32)
+
+
+def expert_bytes_int4(d: int, f: int) -> int:
+    """Bytes of one 4-bit expert: 3 d f codes of 4 bits plus one 16-bit scale per 32 codes (4.5 bits per weight)."""
+    return 3 * d * f // 2 + (3 * d * f // 32) * 2
+
+
 def expert_bytes(d: int, f: int, elem_bytes: int) -> int:
     """Bytes of one expert's three projection matrices (Eq. 3 shapes)."""
     return 3 * d * f * elem_bytes

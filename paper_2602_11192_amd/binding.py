@@ -25,10 +25,10 @@ MOE_ERR_TIMEOUT = -7
 
 MOE_DTYPE_FP32, MOE_DTYPE_BF16 = 0, 1
 MOE_POLICY_LRU, MOE_POLICY_GAMMA = 0, 1
-MOE_LAYOUT_ROWMAJOR, MOE_LAYOUT_TILED = 0, 1
+MOE_LAYOUT_ROWMAJOR, MOE_LAYOUT_TILED, MOE_LAYOUT_TILED_INT4 = 0, 1, 2
 MOE_FETCH_COPY_ENGINE, MOE_FETCH_IN_KERNEL = 0, 1
 
-EXPORTS = ["moe_expert_bytes", "moe_pack_expert", "moe_cache_create", "moe_cache_destroy", "moe_cache_reset",
+EXPORTS = ["moe_expert_bytes", "moe_expert_block_bytes", "moe_pack_expert", "moe_pack_expert_int4", "moe_cache_create", "moe_cache_destroy", "moe_cache_reset",
            "moe_cache_prefill_pins", "moe_layer_decode", "moe_layer_prefill", "moe_cache_stats", "moe_cache_read_trace",
            "moe_cache_resident", "moe_cache_set_profiling", "moe_cache_timing", "moe_probe_stream",
            "moe_cache_sim_loss", "moe_last_error", "moe_version"]
@@ -78,6 +78,9 @@ def _load():
     lib.moe_expert_bytes.argtypes = [i32, i32, i32]
     lib.moe_expert_bytes.restype = C.c_uint64
     lib.moe_pack_expert.argtypes = [vp, vp, i32, i32]
+    lib.moe_expert_block_bytes.argtypes = [i32, i32, i32, i32]
+    lib.moe_expert_block_bytes.restype = C.c_uint64
+    lib.moe_pack_expert_int4.argtypes = [vp, vp, vp, i32, i32]
     lib.moe_cache_create.argtypes = [C.POINTER(moe_cache_config_t), C.POINTER(moe_weights_t), C.POINTER(vp)]
     lib.moe_cache_destroy.argtypes = [vp]
     lib.moe_cache_reset.argtypes = [vp, i32, i32, vp]
@@ -94,7 +97,7 @@ def _load():
     lib.moe_last_error.restype = C.c_char_p
     lib.moe_version.restype = C.c_char_p
     for name in EXPORTS:
-        if name not in ("moe_expert_bytes", "moe_last_error", "moe_version"):
+        if name not in ("moe_expert_bytes", "moe_expert_block_bytes", "moe_last_error", "moe_version"):
             getattr(lib, name).restype = C.c_int
     return lib
 
@@ -124,6 +127,20 @@ def moe_pack_expert(src: np.ndarray, dst: np.ndarray, d_model: int, d_ff: int) -
     assert src.dtype == np.uint16 and dst.dtype == np.uint16
     assert src.size == dst.size == 3 * d_model * d_ff and src.flags.c_contiguous and dst.flags.c_contiguous
     _check(lib.moe_pack_expert(src.ctypes.data, dst.ctypes.data, d_model, d_ff))
+
+
+def moe_expert_block_bytes(d_model: int, d_ff: int, dtype: int, pool_layout: int) -> int:
+    return int(lib.moe_expert_block_bytes(d_model, d_ff, dtype, pool_layout))
+
+
+def moe_pack_expert_int4(codes: np.ndarray, scales: np.ndarray, dst: np.ndarray, d_model: int, d_ff: int) -> None:
+    """codes uint8 [3*d*f] (W_g | W_u | W_d row-major, one code per byte), scales uint16 bf16 bits [3*d*f/32]
+    -> one INT4 tiled block in dst (uint8, moe_expert_block_bytes long), host to host."""
+    assert codes.dtype == np.uint8 and scales.dtype == np.uint16 and dst.dtype == np.uint8
+    assert codes.size == 3 * d_model * d_ff and scales.size * 32 == codes.size
+    assert dst.size == moe_expert_block_bytes(d_model, d_ff, MOE_DTYPE_BF16, MOE_LAYOUT_TILED_INT4)
+    assert codes.flags.c_contiguous and scales.flags.c_contiguous and dst.flags.c_contiguous
+    _check(lib.moe_pack_expert_int4(codes.ctypes.data, scales.ctypes.data, dst.ctypes.data, d_model, d_ff))
 
 
 def moe_probe_stream(src, dst, nbytes: int, mode: int, iters: int = 10, stream=None) -> float:

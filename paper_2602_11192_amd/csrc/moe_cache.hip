@@ -21,6 +21,7 @@
 #include <vector>
 
 #include "moe_internal.hpp"
+#include "q4_layout.hpp"
 
 using namespace moe;
 
@@ -139,7 +140,8 @@ int validate(const moe_cache_config_t* c, const moe_weights_t* w) {
   if (c->max_batch < 1 || c->max_batch > (1 << 20)) return fail(MOE_ERR_INVALID_ARG, "max_batch out of range");
   if (c->staging_buffers < 0 || c->staging_buffers > 1024) return fail(MOE_ERR_INVALID_ARG, "staging_buffers out of range");
   if (c->trace_capacity < 0) return fail(MOE_ERR_INVALID_ARG, "trace_capacity must be >= 0");
-  if (c->pool_layout != MOE_LAYOUT_ROWMAJOR && c->pool_layout != MOE_LAYOUT_TILED)
+  if (c->pool_layout != MOE_LAYOUT_ROWMAJOR && c->pool_layout != MOE_LAYOUT_TILED &&
+      c->pool_layout != MOE_LAYOUT_TILED_INT4)
     return fail(MOE_ERR_INVALID_ARG, "unknown pool_layout");
   if (c->fetch_mode != MOE_FETCH_COPY_ENGINE && c->fetch_mode != MOE_FETCH_IN_KERNEL)
     return fail(MOE_ERR_INVALID_ARG, "unknown fetch_mode");
@@ -153,8 +155,14 @@ int validate(const moe_cache_config_t* c, const moe_weights_t* w) {
   const int vec = c->dtype == MOE_DTYPE_FP32 ? 4 : 8;
   if (c->d_model % vec != 0)
     return fail(MOE_ERR_UNSUPPORTED, "d_model must be a multiple of %d for this dtype", vec);
-  if (c->fetch_mode == MOE_FETCH_IN_KERNEL && (c->pool_layout != MOE_LAYOUT_TILED || c->dtype != MOE_DTYPE_BF16))
-    return fail(MOE_ERR_UNSUPPORTED, "in-kernel fetch needs the tiled bf16 layout");
+  if (c->fetch_mode == MOE_FETCH_IN_KERNEL && (c->pool_layout == MOE_LAYOUT_ROWMAJOR || c->dtype != MOE_DTYPE_BF16))
+    return fail(MOE_ERR_UNSUPPORTED, "in-kernel fetch needs a tiled layout (bf16 activations)");
+  if (c->pool_layout == MOE_LAYOUT_TILED_INT4) {
+    if (c->dtype != MOE_DTYPE_BF16) return fail(MOE_ERR_UNSUPPORTED, "INT4 experts need bf16 activations");
+    if (c->max_batch > 16) return fail(MOE_ERR_UNSUPPORTED, "INT4 experts: max_batch must be <= 16 (decode kernel only)");
+    if (!ffn_fused_q4_supported(c->d_model, c->d_ff, c->max_batch))
+      return fail(MOE_ERR_UNSUPPORTED, "INT4 experts need d_model %% 256 == 0 and d_ff %% 32 == 0");
+  }
   if (c->pool_layout == MOE_LAYOUT_TILED) {
     if (c->dtype != MOE_DTYPE_BF16) return fail(MOE_ERR_UNSUPPORTED, "the tiled layout is bf16 only");
     if (c->d_model % 32 != 0 || c->d_ff % 32 != 0)
@@ -277,6 +285,61 @@ uint64_t moe_expert_bytes(int32_t d_model, int32_t d_ff, int32_t dtype) {
   return (uint64_t)3 * (uint64_t)d_model * (uint64_t)d_ff * (dtype == MOE_DTYPE_FP32 ? 4u : 2u);
 }
 
+uint64_t moe_expert_block_bytes(int32_t d_model, int32_t d_ff, int32_t dtype, int32_t pool_layout) {
+  if (pool_layout == MOE_LAYOUT_TILED_INT4) {
+    if (d_model < 128 || d_ff < 32 || d_model % 128 != 0 || d_ff % 32 != 0) return 0;
+    return q4::block_bytes(d_model, d_ff);
+  }
+  if (pool_layout != MOE_LAYOUT_ROWMAJOR && pool_layout != MOE_LAYOUT_TILED) return 0;
+  return moe_expert_bytes(d_model, d_ff, dtype);
+}
+
+int moe_pack_expert_int4(const uint8_t* codes, const uint16_t* scales, void* dst_block, int32_t d, int32_t f) {
+  if (!codes || !scales || !dst_block) return fail(MOE_ERR_INVALID_ARG, "null pointer");
+  if (d < 128 || f < 32 || d % 128 != 0 || f % 32 != 0)
+    return fail(MOE_ERR_UNSUPPORTED, "d_model must be a positive multiple of 128 and d_ff of 32");
+  for (size_t i = 0; i < (size_t)3 * d * f; ++i)
+    if (codes[i] > 15) return fail(MOE_ERR_INVALID_ARG, "code %u at element %zu is not a 4-bit value", codes[i], i);
+  const size_t df = (size_t)d * f;
+  const uint8_t* cm[3] = {codes, codes + df, codes + 2 * df};
+  const uint16_t* sm[3] = {scales, scales + df / 32, scales + 2 * (df / 32)};
+  char* out = static_cast<char*>(dst_block);
+  auto word = [](const uint8_t* p) {      // eight consecutive codes -> one 32-bit word
+    uint32_t w = 0;
+    for (int e = 0; e < 8; ++e) w |= (uint32_t)p[e] << (4 * q4::nibble_of(e));
+    return w;
+  };
+  const int nsb = d / 128, gd = d / 32, gf = f / 32;
+  for (int rt = 0; rt < f / 16; ++rt)
+    for (int sb = 0; sb < nsb; ++sb) {
+      char* rec = out + ((size_t)rt * nsb + sb) * q4::kGateUpRecord;
+      for (int m = 0; m < 2; ++m)
+        for (int l = 0; l < 64; ++l)
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t w = word(cm[m] + (size_t)(rt * 16 + (l & 15)) * d + sb * 128 + j * 32 + (l >> 4) * 8);
+            memcpy(rec + m * 1024 + l * 16 + j * 4, &w, 4);
+          }
+      for (int r = 0; r < 16; ++r)
+        for (int m = 0; m < 2; ++m)
+          memcpy(rec + 2048 + r * 16 + m * 8, sm[m] + (size_t)(rt * 16 + r) * gd + sb * 4, 8);
+    }
+  char* dsec = out + q4::gate_up_bytes(d, f);
+  const int n_dq = d / 64;
+  for (int c = 0; c < gf; ++c)
+    for (int dq = 0; dq < n_dq; ++dq) {
+      char* rec = dsec + ((size_t)c * n_dq + dq) * q4::kDownRecord;
+      for (int l = 0; l < 64; ++l)
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t w = word(cm[2] + (size_t)(dq * 64 + (l & 15) * 4 + j) * f + c * 32 + (l >> 4) * 8);
+          memcpy(rec + l * 16 + j * 4, &w, 4);
+        }
+      for (int r = 0; r < 16; ++r)
+        for (int j = 0; j < 4; ++j)
+          memcpy(rec + 1024 + r * 8 + j * 2, sm[2] + (size_t)(dq * 64 + r * 4 + j) * gf + c, 2);
+    }
+  return MOE_OK;
+}
+
 int moe_pack_expert(const void* src_rowmajor, void* dst_tiled, int32_t d, int32_t f) {
   if (!src_rowmajor || !dst_tiled) return fail(MOE_ERR_INVALID_ARG, "null pointer");
   if (d < 32 || f < 32 || d % 32 != 0 || f % 32 != 0)
@@ -334,7 +397,7 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->C = std::min(cfg->capacity, E);
   c->P = c->C + cfg->staging_buffers;
   c->KS = K + cfg->n_shared;
-  c->expert_bytes = moe_expert_bytes(cfg->d_model, cfg->d_ff, cfg->dtype);
+  c->expert_bytes = moe_expert_block_bytes(cfg->d_model, cfg->d_ff, cfg->dtype, cfg->pool_layout);
   c->elem = cfg->dtype == MOE_DTYPE_FP32 ? 4 : 2;
   const int C = c->C, P = c->P, KS = c->KS, Bm = cfg->max_batch;
   const size_t NP = (size_t)Bm * KS;
@@ -412,7 +475,8 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->arrive = reinterpret_cast<int32_t*>(c->call_mem + o_arr);
   CREATE_CHK(hipMalloc(&c->h, NP * cfg->d_ff * 4), MOE_ERR_HIP);
   size_t o_bytes = NP * cfg->d_model * 4;
-  if (cfg->pool_layout == MOE_LAYOUT_TILED && ffn_fused_supported(cfg->d_model, cfg->d_ff, 1)) {
+  if (cfg->pool_layout == MOE_LAYOUT_TILED_INT4 ||
+      (cfg->pool_layout == MOE_LAYOUT_TILED && ffn_fused_supported(cfg->d_model, cfg->d_ff, 1))) {
     // the single-launch decode FFN keeps one partial sum per 32-row chunk of d_ff, for calls of up to 16 tokens
     const size_t pairs = (size_t)std::min(Bm, 16) * KS;
     o_bytes = std::max(o_bytes, pairs * (size_t)(cfg->d_ff / 32) * cfg->d_model * 4);
@@ -567,7 +631,8 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   fa.max_count = batch;
   fa.t = c->t; fa.h = c->h; fa.o = c->o;
   const bool tiled = cf.pool_layout == MOE_LAYOUT_TILED;
-  const bool fused = tiled && ffn_fused_supported(d, cf.d_ff, batch);
+  const bool q4w = cf.pool_layout == MOE_LAYOUT_TILED_INT4;
+  const bool fused = q4w || (tiled && ffn_fused_supported(d, cf.d_ff, batch));
   fa.fused = fused ? 1 : 0;
   // Many tokens per expert: token tiles staged in LDS and shared by the waves of a row block.  Below about 32
   // tokens per expert the split-K streaming kernels are faster (measured); the group sizes are not known to the
@@ -583,7 +648,8 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   fa.pool = in_kernel ? c->pool_dev + (size_t)layer * E * c->expert_bytes : nullptr;
   fa.fetch = in_kernel ? 1 : 0;
   fa.pass = in_kernel ? 2 : 0;
-  HIPCHK(fused ? launch_ffn_fused(s, fa, ke1)
+  HIPCHK(q4w ? launch_ffn_fused_q4(s, fa, ke1)
+         : fused ? launch_ffn_fused(s, fa, ke1)
          : gemm ? launch_ffn_gemm(s, fa, ke1, ke2)
          : tiled ? launch_ffn_tiled(s, fa, ke1, ke2)
                  : launch_ffn_rowmajor(s, cf.dtype, fa, ke1, ke2));
@@ -601,7 +667,8 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
     HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0));
     c->copies_pending = false;
     fa.pass = 1;
-    HIPCHK(fused ? launch_ffn_fused(s, fa, KernelEvents{})
+    HIPCHK(q4w ? launch_ffn_fused_q4(s, fa, KernelEvents{})
+           : fused ? launch_ffn_fused(s, fa, KernelEvents{})
            : gemm ? launch_ffn_gemm(s, fa, KernelEvents{}, KernelEvents{})
            : tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
                    : launch_ffn_rowmajor(s, cf.dtype, fa, KernelEvents{}, KernelEvents{}));

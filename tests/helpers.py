@@ -13,14 +13,18 @@ TOL = {"fp32": 1e-4, "bf16": 2e-2}
 class OracleStack:
     """Oracle-side state of a layer stack: float32 parameters and one cache per layer."""
 
-    def __init__(self, wl, capacity=None, policy=oracle.POLICY_LRU, gamma=1.0, keep=40):
-        self.wl, self.cfg = wl, wl.cfg
+    def __init__(self, wl, capacity=None, policy=oracle.POLICY_LRU, gamma=1.0, keep=40, int4=False):
+        self.wl, self.cfg, self.int4 = wl, wl.cfg, int4
         c = self.cfg
         cap = min(c.capacity if capacity is None else capacity, c.n_experts)
         self.caches = [oracle.ExpertCache(c.n_experts, cap, policy, gamma) for _ in range(c.n_layers)]
         self.router = [widen(wl.router_w(l)) for l in range(c.n_layers)]
-        self.shared = [[tuple(widen(m) for m in wl.shared(l, s)) for s in range(c.n_shared)]
-                       for l in range(c.n_layers)]
+        if int4:        # the oracle sees the 4-bit experts through its own dequantisation
+            self.shared = [[tuple(oracle.dequant_int4(q, s) for q, s in wl.shared_int4(l, sh))
+                            for sh in range(c.n_shared)] for l in range(c.n_layers)]
+        else:
+            self.shared = [[tuple(widen(m) for m in wl.shared(l, s)) for s in range(c.n_shared)]
+                           for l in range(c.n_layers)]
         self._experts, self._keep = {}, keep
 
     def expert(self, l, e):
@@ -28,7 +32,10 @@ class OracleStack:
         if key not in self._experts:
             if len(self._experts) >= self._keep:
                 self._experts.pop(next(iter(self._experts)))
-            self._experts[key] = tuple(widen(m) for m in self.wl.expert(l, e))
+            if self.int4:
+                self._experts[key] = tuple(oracle.dequant_int4(q, s) for q, s in self.wl.expert_int4(l, e))
+            else:
+                self._experts[key] = tuple(widen(m) for m in self.wl.expert(l, e))
         return self._experts[key]
 
     def decode(self, l, x32, bias, compute_y=True, norm_topk=None):

@@ -20,7 +20,7 @@ def B():
 def declared_functions():
     text = open(os.path.join(ROOT, "include", "moe_cache.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(B):

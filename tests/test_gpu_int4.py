@@ -1,0 +1,89 @@
+"""MI355X parity of the decode path on 4-bit group-quantised experts (section 3.2 keeps experts in INT4): the HIP
+path sees packed codes and scales, the oracle sees its own dequantisation of the same codes and scales."""
+import numpy as np
+import pytest
+
+import oracle
+from tests.helpers import OracleStack, compare_traces_and_stats, run_sequence_serial
+from tests.test_gpu_parity import batched_step, small_cfg
+from workload import Workload, get_config
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available(), "these tests need the MI355X"
+    return t
+
+
+@pytest.fixture(scope="module")
+def P():
+    from paper_2602_11192_amd import pool
+    return pool
+
+
+def q4_bytes(cfg):
+    return oracle.expert_bytes_int4(cfg.d_model, cfg.d_ff)
+
+
+@pytest.mark.parametrize("fetch", ["copy_engine", "in_kernel"])
+@pytest.mark.parametrize("d_model,d_ff", [(256, 96), (512, 64), (768, 32), (1024, 160)])
+def test_int4_sequence_serial(torch, P, fetch, d_model, d_ff):
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(d_model=d_model, d_ff=d_ff, n_seqs=2, n_steps=16, beta=1.0)
+    wl = Workload(cfg)
+    mode = B.MOE_FETCH_IN_KERNEL if fetch == "in_kernel" else B.MOE_FETCH_COPY_ENGINE
+    cache = P.make_cache(wl, int4=True, trace_capacity=4096, fetch_mode=mode)
+    ost = OracleStack(wl, int4=True)
+    worst, n_y, traces = run_sequence_serial(wl, cache, ost, torch=torch)
+    assert n_y == cfg.n_seqs * cfg.n_steps * cfg.n_layers
+    st = cache.moe_cache_stats()
+    assert st["misses"] > 5 and st["bytes_h2d"] == (st["misses"] + st["pin_loads"]) * q4_bytes(cfg)
+    compare_traces_and_stats(cache, ost, traces, q4_bytes(cfg))
+    cache.close()
+
+
+@pytest.mark.parametrize("fetch", ["copy_engine", "in_kernel"])
+@pytest.mark.parametrize("batch", [2, 5, 16])
+def test_int4_batched_with_shared_experts(torch, P, fetch, batch):
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(d_model=512, d_ff=96, n_seqs=16, n_steps=6, n_layers=1, capacity=7, n_shared=2)
+    wl = Workload(cfg)
+    mode = B.MOE_FETCH_IN_KERNEL if fetch == "in_kernel" else B.MOE_FETCH_COPY_ENGINE
+    cache = P.make_cache(wl, int4=True, max_batch=batch, staging_buffers=batch * cfg.top_k, trace_capacity=8192,
+                         fetch_mode=mode)
+    ost = OracleStack(wl, int4=True)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, list(range(batch)), step))
+    compare_traces_and_stats(cache, ost, traces, q4_bytes(cfg))
+    cache.close()
+
+
+def test_int4_limits_are_reported(torch, P):
+    from paper_2602_11192_amd import binding as B
+    wl = Workload(small_cfg(d_model=256, d_ff=96))
+    with pytest.raises(B.MoeError):
+        P.make_cache(wl, int4=True, max_batch=17)                      # decode kernel only
+    with pytest.raises(B.MoeError):
+        P.make_cache(Workload(small_cfg(d_model=128, d_ff=96)), int4=True)      # d_model % 256 != 0
+    cache = P.make_cache(wl, int4=True)
+    x = torch.zeros((4, 256), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(B.MoeError):
+        cache.moe_layer_prefill(0, x, torch.empty_like(x))             # prompt streaming is bf16 only
+    cache.close()
+
+
+def test_int4_olmoe_like_sampled(torch, P):
+    # full-size layer of the OLMoE-like workload with 4-bit experts: two sequences, outputs checked every 8th step
+    from paper_2602_11192_amd import binding as B
+    cfg = get_config("olmoe_like")
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, int4=True, trace_capacity=1 << 16, fetch_mode=B.MOE_FETCH_IN_KERNEL)
+    ost = OracleStack(wl, int4=True, keep=64)
+    worst, n_y, traces = run_sequence_serial(wl, cache, ost, torch=torch, seqs=[0, 1], steps=64, y_every=8)
+    print("int4 olmoe_like worst rel err", worst, "outputs", n_y)
+    compare_traces_and_stats(cache, ost, traces, q4_bytes(cfg))
+    cache.close()

@@ -6,7 +6,7 @@ MoE layer's or the cache policy's arithmetic; the CPU oracle and the HIP path
 each consume the same arrays and compute everything on their own.
 """
 from .configs import MoEConfig, CONFIGS, get_config
-from .gen import (Workload, f32_to_bf16_bits, bf16_bits_to_f32, widen)
+from .gen import (Workload, f32_to_bf16_bits, bf16_bits_to_f32, widen, quantize_int4)
 
 __all__ = ["MoEConfig", "CONFIGS", "get_config", "Workload",
-           "f32_to_bf16_bits", "bf16_bits_to_f32", "widen"]
+           "f32_to_bf16_bits", "bf16_bits_to_f32", "widen", "quantize_int4"]

@@ -51,6 +51,26 @@ def widen(a: np.ndarray) -> np.ndarray:
     return np.ascontiguousarray(a, dtype=np.float32)
 
 
+INT4_GROUP = 32
+
+
+def quantize_int4(w_store: np.ndarray):
+    """Input recipe for 4-bit experts: a stored bf16 matrix [rows][k] -> (codes uint8 [rows][k] in 0..15,
+    scales uint16 bf16 bits [rows][k/32]).  Per group of 32 consecutive columns the scale is max|w| / 7 rounded to
+    bf16 (1 for an all-zero group) and the code is round(w / scale) + 8, clipped to 0..15.  This only PRODUCES the
+    quantised inputs; what the codes and scales mean (weight = scale * (code - 8)) is implemented separately by the
+    library and by the oracle."""
+    w = bf16_bits_to_f32(w_store).astype(np.float64)
+    rows, k = w.shape
+    assert k % INT4_GROUP == 0
+    g = w.reshape(rows, k // INT4_GROUP, INT4_GROUP)
+    s_bits = f32_to_bf16_bits((np.abs(g).max(axis=-1) / 7.0).astype(np.float32))
+    s_bits[bf16_bits_to_f32(s_bits) == 0.0] = np.uint16(0x3F80)
+    s = bf16_bits_to_f32(s_bits).astype(np.float64)
+    codes = np.clip(np.rint(g / s[..., None]) + 8.0, 0.0, 15.0).astype(np.uint8).reshape(rows, k)
+    return codes, s_bits
+
+
 class Workload:
     def __init__(self, cfg: MoEConfig):
         self.cfg = cfg
@@ -96,6 +116,13 @@ class Workload:
 
     def shared(self, layer: int, s: int):
         return self._ffn(self._rng(_ST_SHARED, layer, s))
+
+    def expert_int4(self, layer: int, e: int):
+        """The same expert quantised to 4 bits: ((codes, scales) of W_g, of W_u, of W_d), see quantize_int4."""
+        return tuple(quantize_int4(m) for m in self.expert(layer, e))
+
+    def shared_int4(self, layer: int, s: int):
+        return tuple(quantize_int4(m) for m in self.shared(layer, s))
 
     def experts_parallel(self, layer: int, ids, workers: int = 8):
         """[(W_g, W_u, W_d)] for several experts, generated on a thread pool."""

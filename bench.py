@@ -40,6 +40,9 @@ def parse():
                     help="how missed experts reach the device (see MOE_FETCH_* in include/moe_cache.h)")
     ap.add_argument("--batch-sweep", metavar="FILE", default=None,
                     help="also time the resident path at batch 1..1024 and write the table to FILE (JSON)")
+    ap.add_argument("--int4", choices=["auto", "on", "off"], default="auto",
+                    help="also run the workload with 4-bit group-quantised experts and report it under "
+                         "'int4_experts' (auto: only when the whole pool has at most 5e8 weights)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain 256 MiB copy kernel (reference dispatch for profiler memory counters)")
     return ap.parse_args()
@@ -145,6 +148,45 @@ def batch_sweep(torch, P, wl, pool, sizes=(1, 2, 4, 8, 16, 32, 64, 128, 256, 512
                      "ffn_kernel": "single-launch decode" if tm["ffn_fused_launches"] else "two kernels"})
         cache.close()
     return {"workload": cfg.name, "layer": 0, "capacity": cfg.n_experts, "rows": rows}
+
+
+def int4_section(torch, P, wl, a):
+    """The same schedule on 4-bit experts (a separate, lower-precision configuration: never the headline value)."""
+    cfg = wl.cfg
+    K, d = cfg.top_k, cfg.d_model
+    qb = P.int4_block_bytes(cfg)
+    pool = P.build_pool(wl, tiled=True, int4=True)
+    cache = P.make_cache(wl, int4=True, pool=pool, fetch_mode=P.B.MOE_FETCH_IN_KERNEL)
+    run = Runner(wl, cache, torch, P)
+    run.pass_sequence_serial()
+    cache.moe_cache_reset(-1, clear_stats=True)
+    n_tok, dt = timed(torch, run.pass_sequence_serial, a.steps)
+    st = cache.moe_cache_stats()
+    cache.moe_cache_set_profiling(True)
+    cache.moe_cache_timing(clear=True)
+    timed(torch, run.pass_sequence_serial, a.steps)
+    tm = cache.moe_cache_timing(clear=True)
+    cache.close()
+    rcache = P.make_cache(wl, int4=True, pool=pool, capacity=cfg.n_experts)
+    rrun = Runner(wl, rcache, torch, P)
+    for l in range(cfg.n_layers):
+        rcache.moe_cache_prefill_pins(l, list(range(cfg.n_experts)))
+    rrun.pass_resident()
+    n_r, dt_r = timed(torch, rrun.pass_resident, a.steps)
+    rcache.close()
+    k_bytes = K * qb + d * 2 + K * d * 4
+    k_ms = tm["ffn_fused_ms"] / max(1, tm["ffn_fused_launches"])
+    return {"format": "groups of 32 along the contraction dimension, 4-bit codes + bf16 scale, weight = s * (q - 8)",
+            "expert_bytes": qb, "tokens_per_s": n_tok / dt,
+            "cache_hit_rate": st["hits"] / max(1, st["lookups"]), "misses_per_token": st["misses"] / max(1, n_tok),
+            "pcie_GBps": tm["fetch_bytes"] / (tm["fetch_ms"] * 1e-3) / 1e9 if tm["fetch_ms"] > 0 else None,
+            "expert_kernel": {"bytes_per_launch": k_bytes, "avg_launch_ms": k_ms,
+                              "launches_timed": tm["ffn_fused_launches"],
+                              "achieved_GBps": k_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else None,
+                              "frac_of_hbm_peak": k_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS if k_ms > 0 else None},
+            "resident_path_tokens_per_s": n_r / dt_r,
+            "note": "same capacity C in experts (a quarter of the bytes); in-kernel fetch; outputs differ from the "
+                    "bf16 run by the quantisation error, parity is against the oracle on the same 4-bit values"}
 
 
 def cpu_baseline(wl, n_tokens):
@@ -333,6 +375,10 @@ def main():
     }
     if a.batch_sweep:
         json.dump(batch_sweep(torch, P, wl, pool), open(a.batch_sweep, "w"), indent=1)
+    n_weights = cfg.n_layers * cfg.n_experts * 3 * d * f
+    if cfg.dtype == "bf16" and (a.int4 == "on" or (a.int4 == "auto" and n_weights <= 5e8)):
+        del pool
+        out["int4_experts"] = int4_section(torch, P, wl, a)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, a.cpu_baseline_tokens)
     print(json.dumps(out))

@@ -44,8 +44,8 @@ typedef enum {
   MOE_ERR_CAPACITY_LT_TOPK = -2,   /* capacity < top_k: one token's experts would not fit    */
   MOE_ERR_OUT_OF_MEMORY = -3,      /* host or device allocation failed                       */
   MOE_ERR_HIP = -4,                /* a HIP runtime call failed (text in moe_last_error)     */
-  MOE_ERR_STAGING_EXHAUSTED = -5,  /* a batched call needed more spare expert buffers than
-                                      `staging_buffers`; the cache state is left unchanged   */
+  MOE_ERR_STAGING_EXHAUSTED = -5,  /* no expert buffer left for a load (prefill_pins); the
+                                      cache state is left unchanged                          */
   MOE_ERR_UNSUPPORTED = -6,        /* shape / layout combination without a kernel            */
   MOE_ERR_TIMEOUT = -7             /* the device did not report the miss list in time        */
 } moe_status_t;
@@ -132,7 +132,7 @@ typedef struct {
 
 /* One lookup, in the order the lookups were made. */
 typedef struct {
-  int32_t token;   /* row of the batch the lookup belongs to                                */
+  int32_t token;   /* row of the moe_layer_decode call the lookup belongs to                */
   int32_t expert;  /* expert id                                                             */
   int32_t hit;     /* 1 = resident, 0 = fetched                                             */
   int32_t evicted; /* expert dropped to make room, -1 if none                               */
@@ -219,12 +219,28 @@ int moe_cache_prefill_pins(moe_cache_t* cache, int32_t layer, const int32_t* exp
  *   topk_idx_dev   device, [batch][K] int32, selected experts in ascending id; may be NULL
  *   topk_w_dev     device, [batch][K] fp32 gate weights aligned with topk_idx; may be NULL
  * Tokens are looked up in row order and, within a token, in ascending expert id.
- * Errors: INVALID_ARG (null x/y, batch < 1 or > max_batch, layer out of range),
- * STAGING_EXHAUSTED, HIP, TIMEOUT.
+ * A call whose evictions would need more spare buffers than `staging_buffers` provides
+ * is executed as consecutive waves of tokens (the batch is halved until every wave
+ * fits; one token always fits); routing, hits, misses, evictions and outputs are the
+ * same as for the unsplit call, only slower.
+ * Errors: INVALID_ARG (null x/y, batch < 1 or > max_batch, layer out of range), HIP, TIMEOUT.
  */
 int moe_layer_decode(moe_cache_t* cache, int32_t layer, const void* x_dev,
                      const float* logit_bias_dev, int32_t batch, void* y_dev,
                      int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
+
+/*
+ * Prefetch set for a cache shared by several sequences (section 3.2 forms, per layer, the
+ * set Top-C of the predictor's scores for one sequence; for a batch of sequences decoded
+ * together the scores are summed over the sequences first).  Host-side helper.
+ *   scores   host, [n_seqs][n_experts] fp32, summed per expert in fp64 in row order
+ *   ids_out  host, [min(capacity, n_experts)]: the selected experts, lowest total first, so
+ *            that passing the list to moe_cache_prefill_pins leaves the best-scored expert
+ *            most recently used; equal totals rank the lower id higher
+ *   n_out    number of ids written
+ */
+int moe_pooled_prefetch_set(const float* scores, int32_t n_seqs, int32_t n_experts, int32_t capacity,
+                            int32_t* ids_out, int32_t* n_out);
 
 /*
  * Prompt processing in streaming mode.  The paper places the prefetch "before generation begins"

@@ -315,6 +315,18 @@ def cache_sim_loss(idx, n_experts: int, capacity: int, gamma: float, c1=None):
     return soft_sum / (L * T), hard_sum / (L * T)
 
 
+def pooled_prefetch_set(scores, capacity: int) -> list:
+    """Prefetch set of a cache shared by several sequences: section 3.2's Top-C of the predictor's scores, applied
+    to the scores summed over the sequences (fp64, in row order).  Returned lowest total first, so that pinning in
+    list order leaves the best-scored expert most recently used; equal totals rank the lower id higher."""
+    scores = np.asarray(scores, dtype=np.float32)
+    total = np.zeros(scores.shape[1], dtype=np.float64)
+    for row in scores:
+        total = total + row.astype(np.float64)
+    ranked = sorted(range(scores.shape[1]), key=lambda e: (-total[e], e))
+    return ranked[:min(capacity, scores.shape[1])][::-1]
+
+
 def dequant_int4(codes, scale_bits) -> np.ndarray:
     """4-bit group-quantised matrix -> its weights (section 3.2 keeps experts in INT4; the format here is the
     generic symmetric one: 32 consecutive elements of a row share one bf16 scale, weight = scale * (code - 8)).

@@ -31,7 +31,7 @@ MOE_FETCH_COPY_ENGINE, MOE_FETCH_IN_KERNEL = 0, 1
 EXPORTS = ["moe_expert_bytes", "moe_expert_block_bytes", "moe_pack_expert", "moe_pack_expert_int4", "moe_cache_create", "moe_cache_destroy", "moe_cache_reset",
            "moe_cache_prefill_pins", "moe_layer_decode", "moe_layer_prefill", "moe_cache_stats", "moe_cache_read_trace",
            "moe_cache_resident", "moe_cache_set_profiling", "moe_cache_timing", "moe_probe_stream",
-           "moe_cache_sim_loss", "moe_last_error", "moe_version"]
+           "moe_cache_sim_loss", "moe_pooled_prefetch_set", "moe_last_error", "moe_version"]
 
 
 class moe_cache_config_t(C.Structure):
@@ -94,6 +94,7 @@ def _load():
     lib.moe_cache_timing.argtypes = [vp, C.POINTER(moe_timing_t), i32]
     lib.moe_probe_stream.argtypes = [vp, vp, C.c_uint64, i32, i32, vp, C.POINTER(C.c_double)]
     lib.moe_cache_sim_loss.argtypes = [vp, i32, i32, i32, i32, i32, C.c_double, vp, vp, vp, vp]
+    lib.moe_pooled_prefetch_set.argtypes = [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.moe_last_error.restype = C.c_char_p
     lib.moe_version.restype = C.c_char_p
     for name in EXPORTS:
@@ -141,6 +142,16 @@ def moe_pack_expert_int4(codes: np.ndarray, scales: np.ndarray, dst: np.ndarray,
     assert dst.size == moe_expert_block_bytes(d_model, d_ff, MOE_DTYPE_BF16, MOE_LAYOUT_TILED_INT4)
     assert codes.flags.c_contiguous and scales.flags.c_contiguous and dst.flags.c_contiguous
     _check(lib.moe_pack_expert_int4(codes.ctypes.data, scales.ctypes.data, dst.ctypes.data, d_model, d_ff))
+
+
+def moe_pooled_prefetch_set(scores: np.ndarray, capacity: int) -> list:
+    """scores [n_seqs][E] float32 -> ids of the Top-capacity experts by summed score, best last."""
+    scores = np.ascontiguousarray(scores, dtype=np.float32)
+    n_seqs, E = scores.shape
+    ids = (C.c_int32 * min(capacity, E))()
+    n = C.c_int32()
+    _check(lib.moe_pooled_prefetch_set(scores.ctypes.data, n_seqs, E, capacity, ids, C.byref(n)))
+    return list(ids[:n.value])
 
 
 def moe_probe_stream(src, dst, nbytes: int, mode: int, iters: int = 10, stream=None) -> float:

@@ -43,7 +43,16 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // displacing the router matrix, the tokens and the partial sums from L2 / Infinity Cache
 // (measured: +8 % on the 700 MB Mixtral-like call, and the router kernel of the next
 // call finds its matrix still cached).
-__device__ __forceinline__ u32x4 ldw(const u32x4* p) { return __builtin_nontemporal_load(p); }
+#ifndef MOE_FUSED_NT
+#define MOE_FUSED_NT 1
+#endif
+__device__ __forceinline__ u32x4 ldw(const u32x4* p) {
+#if MOE_FUSED_NT
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
 
 __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
   return id < a.P ? a.buffers + (size_t)id * a.expert_bytes

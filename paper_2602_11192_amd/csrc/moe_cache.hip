@@ -81,6 +81,7 @@ struct moe_cache {
   void* h = nullptr;
   float* o = nullptr;
   int32_t* arrive = nullptr;
+  uint64_t wave_splits = 0;         // calls that had to be run as two waves of tokens
   const char* pool_dev = nullptr;   // the pinned pool as the device sees it (in-kernel fetch)
 
   char* host_mem = nullptr;       // pinned: mailbox | pin ids | miss list
@@ -583,17 +584,13 @@ int moe_cache_prefill_pins(moe_cache_t* c, int32_t layer, const int32_t* expert_
   return MOE_OK;
 }
 
-int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const float* logit_bias_dev, int32_t batch,
-                     void* y_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
-  if (!c) return fail(MOE_ERR_INVALID_ARG, "null cache");
-  if (layer < 0 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
-  if (!x_dev || !y_dev) return fail(MOE_ERR_INVALID_ARG, "x_dev and y_dev must not be null");
-  if (batch < 1 || batch > c->cfg.max_batch)
-    return fail(MOE_ERR_INVALID_ARG, "batch %d outside 1..max_batch=%d", batch, c->cfg.max_batch);
-  if (reinterpret_cast<uintptr_t>(x_dev) & 15) return fail(MOE_ERR_INVALID_ARG, "x_dev must be 16-byte aligned");
-  DeviceGuard guard;
-  HIPCHK(guard.enter(c->device));
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+}  // extern "C"
+
+namespace {
+
+// One wave of tokens: the whole call when its evictions fit the spare buffers.
+int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* logit_bias_dev, int32_t batch,
+                void* y_dev, int32_t* topk_idx_dev, float* topk_w_dev, hipStream_t s, int32_t row0) {
   const moe_cache_config_t& cf = c->cfg;
   const int E = cf.n_experts, K = cf.top_k, KS = c->KS, d = cf.d_model;
 
@@ -615,6 +612,7 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
 
   CacheCallArgs a{};
   a.mode = 0; a.B = batch; a.K = K; a.KS = KS; a.E = E; a.C = c->C; a.P = c->P; a.n_shared = cf.n_shared;
+  a.row0 = row0;
   a.policy = cf.policy; a.gamma = cf.gamma; a.trace_cap = cf.trace_capacity; a.seq = ++c->seq;
   a.pin_ids = nullptr; a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
   HIPCHK(launch_route_cache(s, cf.dtype, ra, c->layers[layer], c->t, a, ps ? ps->route : KernelEvents{}));
@@ -686,6 +684,57 @@ int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const flo
   st.misses += (uint64_t)mb.n_miss;
   st.evictions += (uint64_t)mb.n_evict;
   st.bytes_h2d += (uint64_t)mb.n_miss * c->expert_bytes;
+  return MOE_OK;
+}
+
+// A call whose evictions need more spare buffers than exist changes nothing on the device; it is then run as two
+// consecutive waves of tokens (recursively).  Tokens are looked up in row order either way, so hits, misses,
+// evictions and outputs are those of the unsplit call.  A single token always fits (K <= C).
+int decode_rows(moe_cache_t* c, int32_t layer, const char* x, const float* bias, int32_t batch, char* y,
+                int32_t* idx, float* w, hipStream_t s, int32_t row0) {
+  const int rc = decode_wave(c, layer, x, bias, batch, y, idx, w, s, row0);
+  if (rc != MOE_ERR_STAGING_EXHAUSTED || batch == 1) return rc;
+  ++c->wave_splits;
+  const int n1 = batch / 2;
+  const size_t row = (size_t)c->cfg.d_model * c->elem;
+  const int E = c->cfg.n_experts, K = c->cfg.top_k;
+  const int rc1 = decode_rows(c, layer, x, bias, n1, y, idx, w, s, row0);
+  if (rc1 != MOE_OK) return rc1;
+  return decode_rows(c, layer, x + n1 * row, bias ? bias + (size_t)n1 * E : nullptr, batch - n1, y + n1 * row,
+                     idx ? idx + (size_t)n1 * K : nullptr, w ? w + (size_t)n1 * K : nullptr, s, row0 + n1);
+}
+
+}  // namespace
+
+extern "C" {
+
+int moe_layer_decode(moe_cache_t* c, int32_t layer, const void* x_dev, const float* logit_bias_dev, int32_t batch,
+                     void* y_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream) {
+  if (!c) return fail(MOE_ERR_INVALID_ARG, "null cache");
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  if (!x_dev || !y_dev) return fail(MOE_ERR_INVALID_ARG, "x_dev and y_dev must not be null");
+  if (batch < 1 || batch > c->cfg.max_batch)
+    return fail(MOE_ERR_INVALID_ARG, "batch %d outside 1..max_batch=%d", batch, c->cfg.max_batch);
+  if (reinterpret_cast<uintptr_t>(x_dev) & 15) return fail(MOE_ERR_INVALID_ARG, "x_dev must be 16-byte aligned");
+  DeviceGuard guard;
+  HIPCHK(guard.enter(c->device));
+  return decode_rows(c, layer, static_cast<const char*>(x_dev), logit_bias_dev, batch, static_cast<char*>(y_dev),
+                     topk_idx_dev, topk_w_dev, static_cast<hipStream_t>(hip_stream), 0);
+}
+
+int moe_pooled_prefetch_set(const float* scores, int32_t n_seqs, int32_t n_experts, int32_t capacity,
+                            int32_t* ids_out, int32_t* n_out) {
+  if (!scores || !ids_out || !n_out) return fail(MOE_ERR_INVALID_ARG, "null pointer");
+  if (n_seqs < 1 || n_experts < 1 || capacity < 1) return fail(MOE_ERR_INVALID_ARG, "sizes must be positive");
+  std::vector<double> total((size_t)n_experts, 0.0);
+  for (int sq = 0; sq < n_seqs; ++sq)
+    for (int e = 0; e < n_experts; ++e) total[e] += (double)scores[(size_t)sq * n_experts + e];
+  std::vector<int32_t> order((size_t)n_experts);
+  for (int e = 0; e < n_experts; ++e) order[e] = e;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return total[a] > total[b]; });
+  const int n = std::min(capacity, n_experts);
+  for (int i = 0; i < n; ++i) ids_out[i] = order[n - 1 - i];     // best score last = most recently used
+  *n_out = n;
   return MOE_OK;
 }
 

@@ -73,6 +73,7 @@ struct CacheCallArgs {
   Mailbox* mailbox;       // host-mapped
   MissEntry* miss_list;   // host-mapped, [max_miss]
   int32_t max_miss;
+  int32_t row0;           // row of the caller's batch at which this wave of tokens starts (trace records)
 };
 
 struct FfnArgs {

@@ -464,7 +464,7 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
       if (a.mode == 0) {
         pair_buf[(size_t)b * KS + k] = buf;
         if (trace_n + trace_added < a.trace_cap)
-          st.trace[trace_n + trace_added] = moe_trace_rec_t{b, e, hit ? 1 : 0, evicted};
+          st.trace[trace_n + trace_added] = moe_trace_rec_t{a.row0 + b, e, hit ? 1 : 0, evicted};
       }
     }
     if (a.mode == 0) ++trace_added;
@@ -629,7 +629,7 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
       const int my_slot = valid ? lds_slot_of[my_e] : 0;
       if (valid) atomicMax(&lds_last[my_slot], l + 1);
       const int my_buf = __shfl(f.buf, my_slot);
-      if (valid && f.trace_n + l < a.trace_cap) st.trace[f.trace_n + l] = moe_trace_rec_t{l / K, my_e, 1, -1};
+      if (valid && f.trace_n + l < a.trace_cap) st.trace[f.trace_n + l] = moe_trace_rec_t{a.row0 + l / K, my_e, 1, -1};
       if (small) {
         // lane p = b*KS + k takes the buffer of lookup b*K + k (a single step)
         const int b = lane / KS, k = lane - b * KS;
@@ -694,7 +694,7 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
         if (lane == buf) f.used = seq;
         if (lane == q) my_buf = buf;
         if (a.mode == 0 && lane == 0 && f.trace_n + chunk0 + q < a.trace_cap)
-          st.trace[f.trace_n + chunk0 + q] = moe_trace_rec_t{(chunk0 + q) / K, e, hit ? 1 : 0, evicted};
+          st.trace[f.trace_n + chunk0 + q] = moe_trace_rec_t{a.row0 + (chunk0 + q) / K, e, hit ? 1 : 0, evicted};
       }
     }
     if (a.mode == 0 && status == MOE_OK) {

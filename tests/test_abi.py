@@ -131,3 +131,18 @@ def test_pack_expert_is_the_documented_permutation(B):
     assert sorted(dst.tolist()) == sorted(src.tolist())
     bad = np.zeros(3 * 48 * 64, dtype=np.uint16)
     assert B.lib.moe_pack_expert(bad.ctypes.data, bad.ctypes.data, 48, 64) == B.MOE_ERR_UNSUPPORTED
+
+
+def test_pooled_prefetch_set_hand_example_and_oracle(B):
+    import oracle
+    # totals: e0 = 1.0, e1 = 3.0, e2 = 3.0, e3 = 0.5 -> ranking 1, 2 (tie: lower id first), 0, 3
+    scores = np.array([[1.0, 1.0, 2.0, 0.5], [0.0, 2.0, 1.0, 0.0]], dtype=np.float32)
+    assert B.moe_pooled_prefetch_set(scores, 3) == [0, 2, 1] == oracle.pooled_prefetch_set(scores, 3)
+    assert B.moe_pooled_prefetch_set(scores, 9) == [3, 0, 2, 1]
+    r = np.random.default_rng(3)
+    for _ in range(20):
+        sc = r.integers(0, 4, size=(5, 17)).astype(np.float32)        # many ties
+        cap = int(r.integers(1, 20))
+        assert B.moe_pooled_prefetch_set(sc, cap) == oracle.pooled_prefetch_set(sc, cap)
+    with pytest.raises(B.MoeError):
+        B.moe_pooled_prefetch_set(scores, 0)

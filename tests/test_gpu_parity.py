@@ -247,23 +247,44 @@ def test_prompt_streaming_reads_the_cache_without_changing_it(torch, P, n_tokens
     cache.close()
 
 
-def test_staging_exhausted_leaves_cache_unchanged(torch, P):
-    from paper_2602_11192_amd import binding as B
-    cfg = small_cfg(n_seqs=8, n_steps=4, n_layers=1, capacity=4, pref_lo=0, pref_hi=0, beta=0.0)
+@pytest.mark.parametrize("staging", [0, 3])
+@pytest.mark.parametrize("tiled", [False, True])
+def test_calls_that_do_not_fit_the_spare_buffers_run_as_waves(torch, P, tiled, staging):
+    # 8 tokens x K = 4 lookups against 4 slots and few spare buffers: the call is split into waves of tokens;
+    # trace, statistics and outputs equal the oracle's, which knows nothing of buffers
+    cfg = small_cfg(n_seqs=8, n_steps=6, n_layers=1, capacity=4, pref_lo=0, pref_hi=0, beta=0.0)
     wl = Workload(cfg)
-    cache = P.make_cache(wl, tiled=True, max_batch=8, staging_buffers=0, trace_capacity=512)
+    cache = P.make_cache(wl, tiled=tiled, max_batch=8, staging_buffers=staging, trace_capacity=1024)
     ost = OracleStack(wl)
-    trace = batched_step(torch, P, wl, cache, ost, 0, [0], 0)          # a call that fits
-    before = (cache.moe_cache_resident(0), cache.moe_cache_stats(0), cache.moe_cache_read_trace(0)[1])
-    xs = np.stack([wl.tokens(s)[1] for s in range(8)])
-    y = torch.empty((8, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
-    with pytest.raises(B.MoeError) as ei:
-        cache.moe_layer_decode(0, P.to_device(xs), y)
-    assert ei.value.code == B.MOE_ERR_STAGING_EXHAUSTED
-    torch.cuda.synchronize()
-    assert (cache.moe_cache_resident(0), cache.moe_cache_stats(0), cache.moe_cache_read_trace(0)[1]) == before
-    trace += batched_step(torch, P, wl, cache, ost, 0, [1], 1)          # and the cache still works
-    compare_traces_and_stats(cache, ost, [trace], cfg.expert_bytes)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        rows = list(range(8)) if step % 2 == 0 else [1, 4, 6]
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, rows, step))
+    assert cache.moe_cache_stats(0)["evictions"] > 20
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+def test_shared_cache_with_pooled_prefetch(torch, P):
+    # 6 sequences decode together on one cache, preloaded with the Top-C of their summed preference scores
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(n_seqs=6, n_steps=10, n_layers=2, capacity=8, beta=2.5)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=True, max_batch=6, staging_buffers=4, trace_capacity=4096)
+    ost = OracleStack(wl)
+    for l in range(cfg.n_layers):
+        scores = np.stack([wl.bias(l, s) for s in range(6)])
+        ids = B.moe_pooled_prefetch_set(scores, cfg.capacity)
+        assert ids == oracle.pooled_prefetch_set(scores, cfg.capacity)
+        cache.moe_cache_prefill_pins(l, ids)
+        ost.caches[l].pin(ids)
+    traces = [[], []]
+    for step in range(cfg.n_steps):
+        for l in range(cfg.n_layers):
+            traces[l].extend(batched_step(torch, P, wl, cache, ost, l, list(range(6)), step))
+    st = cache.moe_cache_stats()
+    assert st["pin_loads"] == 16 and st["hits"] > st["misses"]
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
     cache.close()
 
 

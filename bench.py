@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--int4", choices=["auto", "on", "off"], default="auto",
                     help="also run the workload with 4-bit group-quantised experts and report it under "
                          "'int4_experts' (auto: only when the whole pool has at most 5e8 weights)")
+    ap.add_argument("--extras", metavar="FILE", default=None,
+                    help="also measure the widened rows (eviction policies, shared-cache batched decode with pooled "
+                         "prefetch, prompt streaming, cache-simulation loss) and write them to FILE (JSON)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain 256 MiB copy kernel (reference dispatch for profiler memory counters)")
     return ap.parse_args()
@@ -148,6 +151,114 @@ def batch_sweep(torch, P, wl, pool, sizes=(1, 2, 4, 8, 16, 32, 64, 128, 256, 512
                      "ffn_kernel": "single-launch decode" if tm["ffn_fused_launches"] else "two kernels"})
         cache.close()
     return {"workload": cfg.name, "layer": 0, "capacity": cfg.n_experts, "rows": rows}
+
+
+def extras(torch, P, wl, pool, a):
+    """Measurements of the rows beyond the batch-1 LRU decode step, on the same workload (layer stack as given)."""
+    import numpy as np
+    B = P.B
+    cfg = wl.cfg
+    K, E, S = cfg.top_k, cfg.n_experts, cfg.n_seqs
+    out = {"workload": cfg.name}
+
+    # eviction policies on the sequence-serial schedule (Definition C.1: gamma -> 0 is LRU, gamma = 1 is LFU)
+    pol = []
+    for name, policy, gamma in (("LRU", B.MOE_POLICY_LRU, 0.0), ("gamma=1 (LFU)", B.MOE_POLICY_GAMMA, 1.0),
+                                ("gamma=0.9", B.MOE_POLICY_GAMMA, 0.9)):
+        cache = P.make_cache(wl, tiled=True, pool=pool, fetch_mode=B.MOE_FETCH_IN_KERNEL, policy=policy, gamma=gamma)
+        run = Runner(wl, cache, torch, P)
+        run.pass_sequence_serial()
+        cache.moe_cache_reset(-1, clear_stats=True)
+        n, dt = timed(torch, run.pass_sequence_serial, 2)
+        st = cache.moe_cache_stats()
+        pol.append({"policy": name, "tokens_per_s": n / dt, "hit_rate": st["hits"] / max(1, st["lookups"]),
+                    "misses_per_token": st["misses"] / n})
+        cache.close()
+    out["eviction_policies"] = pol
+
+    # all sequences decode together on one cache per layer, preloaded with the pooled prefetch set
+    rows = []
+    xs = [P.to_device(np.stack([wl.tokens(s)[t] for s in range(S)])) for t in range(cfg.n_steps)]
+    bias = [torch.from_numpy(np.stack([wl.bias(l, s) for s in range(S)])).cuda() for l in range(cfg.n_layers)]
+    y = torch.empty((S, cfg.d_model), dtype=P.torch_dtype(cfg), device="cuda:0")
+    for cap in sorted({cfg.capacity, min(E, 2 * cfg.capacity), E}):
+        cache = P.make_cache(wl, tiled=True, pool=pool, capacity=cap, max_batch=S, staging_buffers=min(E - cap, S * K),
+                             fetch_mode=B.MOE_FETCH_IN_KERNEL)
+        sets = [B.moe_pooled_prefetch_set(np.stack([wl.bias(l, s) for s in range(S)]), cap)
+                for l in range(cfg.n_layers)]
+
+        def one_pass():
+            cache.moe_cache_reset(-1)
+            for l in range(cfg.n_layers):
+                cache.moe_cache_prefill_pins(l, sets[l])
+            for t in range(cfg.n_steps):
+                for l in range(cfg.n_layers):
+                    cache.moe_layer_decode(l, xs[t], y, bias[l])
+            return S * cfg.n_steps
+
+        one_pass()
+        cache.moe_cache_reset(-1, clear_stats=True)
+        n, dt = timed(torch, one_pass, 2)
+        st = cache.moe_cache_stats()
+        rows.append({"capacity": cap, "batch": S, "tokens_per_s": n / dt,
+                     "hit_rate": st["hits"] / max(1, st["lookups"]), "misses_per_call": st["misses"] / (2 * cfg.n_steps * cfg.n_layers)})
+        cache.close()
+    out["shared_cache_batched_decode"] = rows
+
+    # prompt streaming: a prompt through every layer with the cache read-only (missing experts read from the pool)
+    n_p = min(512, S * cfg.n_steps)
+    toks = np.concatenate([wl.tokens(s) for s in range(S)])[:n_p]
+    xp = P.to_device(toks)
+    yp = torch.empty((n_p, cfg.d_model), dtype=P.torch_dtype(cfg), device="cuda:0")
+    cache = P.make_cache(wl, tiled=True, pool=pool, max_batch=n_p)
+    for l in range(cfg.n_layers):
+        cache.moe_cache_prefill_pins(l, wl.prefetch_list(l, 0))
+
+    def prompt_pass():
+        for l in range(cfg.n_layers):
+            cache.moe_layer_prefill(l, xp, yp)
+        return n_p
+
+    prompt_pass()
+    cache.moe_cache_reset(-1, clear_stats=True)
+    for l in range(cfg.n_layers):
+        cache.moe_cache_prefill_pins(l, wl.prefetch_list(l, 0))
+    n, dt = timed(torch, prompt_pass, 3)
+    st = cache.moe_cache_stats()
+    out["prompt_streaming"] = {"prompt_tokens": n_p, "tokens_per_s": n / dt, "ms_per_layer": dt / 3 / cfg.n_layers * 1e3,
+                               "experts_streamed_per_layer": st["stream_loads"] / (3 * cfg.n_layers),
+                               "pcie_GBps_lower_bound": st["bytes_streamed"] / dt / 1e9,
+                               "ffn_TFLOPs_incl_routing": 6.0 * cfg.d_model * cfg.d_ff * n_p * (K + cfg.n_shared) * 3 * cfg.n_layers / dt / 1e12}
+    cache.close()
+
+    # cache-simulation loss of the routing traces of the workload (one trace per sequence and layer)
+    idx_all = torch.empty((S, cfg.n_steps, K), dtype=torch.int32, device="cuda:0")
+    cache = P.make_cache(wl, tiled=True, pool=pool, capacity=E, max_batch=S)
+    cache.moe_cache_prefill_pins(0, list(range(E)))
+    idx_t = torch.empty((S, K), dtype=torch.int32, device="cuda:0")
+    for t in range(cfg.n_steps):
+        cache.moe_layer_decode(0, xs[t], y, bias[0], idx_t)
+        idx_all[:, t, :] = idx_t
+    cache.close()
+    reps = 64
+    big = idx_all.repeat(reps, 1, 1).contiguous()                  # reps * S traces
+    outb, flag = B.moe_cache_sim_loss(big, E, cfg.capacity, 0.9)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        B.moe_cache_sim_loss(big, E, cfg.capacity, 0.9, out=outb, flag=flag)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 10
+    res = outb[:S].cpu().numpy()
+    out["cache_simulation_loss"] = {"traces": reps * S, "tokens_per_trace": cfg.n_steps, "gamma": 0.9,
+                                    "capacity": cfg.capacity, "ms_per_launch": ms,
+                                    "token_steps_per_s": reps * S * cfg.n_steps / (ms * 1e-3),
+                                    "L_cs": float(res[:, 0].sum() / (S * cfg.n_steps)),
+                                    "L_cs_hard": float(res[:, 1].sum() / (S * cfg.n_steps)),
+                                    "note": "layer 0 routing of the workload; uniform first state"}
+    return out
 
 
 def int4_section(torch, P, wl, a):
@@ -375,6 +486,8 @@ def main():
     }
     if a.batch_sweep:
         json.dump(batch_sweep(torch, P, wl, pool), open(a.batch_sweep, "w"), indent=1)
+    if a.extras:
+        json.dump(extras(torch, P, wl, pool, a), open(a.extras, "w"), indent=1)
     n_weights = cfg.n_layers * cfg.n_experts * 3 * d * f
     if cfg.dtype == "bf16" and (a.int4 == "on" or (a.int4 == "auto" and n_weights <= 5e8)):
         del pool

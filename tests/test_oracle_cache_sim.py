@@ -67,10 +67,18 @@ def test_constant_routing_closed_form_and_bounds():
         Gamma = gamma ** (t - 1) + (K / C) * geo
         expect += K - (K * geo + gamma ** (t - 1) * K * C / E) / Gamma
     assert soft == pytest.approx(expect / T, rel=1e-13)
-    idx2 = trace(3, 3, 60, 4, 32, zipf=0.7)
-    for g in (0.0, 0.3, 0.9, 1.0):
-        s, h = oracle.cache_sim_loss(idx2, 32, 8, g)
-        assert 0.0 <= s <= 4.0 and 0.0 <= h <= 4.0
+    # the soft state has L1 norm C and K requested entries, so <r, c> <= C: K - C <= L_cs <= K (the soft loss goes
+    # negative for concentrated routing: entries of c grow up to C / K); the hard count lies in [0, K]
+    for zipf in (0.7, 3.0):
+        idx2 = trace(3, 3, 60, 4, 32, zipf=zipf)
+        for g in (0.0, 0.3, 0.9, 1.0):
+            s, h = oracle.cache_sim_loss(idx2, 32, 8, g)
+            assert 4.0 - 8.0 <= s <= 4.0 and 0.0 <= h <= 4.0
+    # constant routing drives the requested entries to C / K each: the per-token loss tends to K - C
+    long_idx = np.tile(np.array([2, 7], dtype=np.int32), (1, 400, 1))
+    s_all, _ = oracle.cache_sim_loss(long_idx, E, C, gamma)
+    s_head, _ = oracle.cache_sim_loss(long_idx[:, :200], E, C, gamma)
+    assert (400 * s_all - 200 * s_head) / 200 == pytest.approx(K - C, abs=1e-9)
 
 
 def test_constant_routing_hard_count_by_hand():

@@ -285,7 +285,7 @@ def int4_section(torch, P, wl, a):
     rrun.pass_resident()
     n_r, dt_r = timed(torch, rrun.pass_resident, a.steps)
     rcache.close()
-    k_bytes = K * qb + d * 2 + K * d * 4
+    k_bytes = (K + cfg.n_shared) * qb + d * 2 + (K + cfg.n_shared) * d * 4
     k_ms = tm["ffn_fused_ms"] / max(1, tm["ffn_fused_launches"])
     return {"format": "groups of 32 along the contraction dimension, 4-bit codes + bf16 scale, weight = s * (q - 8)",
             "expert_bytes": qb, "tokens_per_s": n_tok / dt,
@@ -426,15 +426,17 @@ def main():
     rcache.close()
 
     # ---------------- roofline of the dominant kernel: the expert FFN of the K selected experts ----------------
-    # algorithmic bytes of one launch at batch 1: the three matrices of K experts, the token in, K partial rows out
+    # algorithmic bytes of one launch at batch 1: the three matrices of the K selected (and the always-active shared)
+    # experts, the token in, one output row per expert out
+    KS_ = K + cfg.n_shared
     fused = tm["ffn_fused_launches"] > 0
     if fused:
-        k_bytes = K * 3 * d * f * s_el + d * s_el + K * d * 4
+        k_bytes = KS_ * 3 * d * f * s_el + d * s_el + KS_ * d * 4
         k_ms = tm["ffn_fused_ms"] / max(1, tm["ffn_fused_launches"])
         k_n = tm["ffn_fused_launches"]
         k_name = "ffn_fused_kernel (gate/up + SiLU*mul + down projection of the K selected experts, one launch)"
     else:
-        k_bytes = K * 2 * d * f * s_el + d * s_el + K * f * s_el
+        k_bytes = KS_ * 2 * d * f * s_el + d * s_el + KS_ * f * s_el
         k_ms = tm["ffn_gate_up_ms"] / max(1, tm["ffn_launches"])
         k_n = tm["ffn_launches"]
         k_name = "ffn_tiled_kernel<2,...> (gate/up + SiLU*mul of the K selected experts)"
@@ -451,7 +453,7 @@ def main():
                           "(hipExtLaunchKernelGGL start/stop), same steps re-run with event timing on; "
                           "launches of calls without a miss"}
 
-    layer_bytes = K * eb + cfg.n_experts * d * s_el + 2 * d * s_el + cfg.n_experts * 4
+    layer_bytes = (K + cfg.n_shared) * eb + cfg.n_experts * d * s_el + 2 * d * s_el + cfg.n_experts * 4
     res_tok_s = n_tok_r / dt_r
     ffn_ms_r = ((rtm["ffn_gate_up_ms"] + rtm["ffn_down_ms"] + rtm["ffn_fused_ms"]) /
                 max(1, rtm["ffn_launches"] + rtm["ffn_fused_launches"]))

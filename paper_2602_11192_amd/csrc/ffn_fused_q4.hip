@@ -37,8 +37,18 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kDepthA = 4;   // gate/up items (2.25 KiB each) a wave keeps in flight
-constexpr int kDepthB = 8;   // W_d items (1.125 KiB each)
+// Items a wave keeps in flight.  Shallow on purpose: the unpacked operands and the MFMA chains of four k-blocks
+// already take ~100 registers, and staying under 128 lets two workgroups share a compute unit, which hides the
+// start-up and the LDS reduction of one behind the streaming of the other (measured: 64 -> 47 us on the
+// Mixtral-like shape against rings of 4 and 8).
+#ifndef MOE_Q4_DEPTH_A
+#define MOE_Q4_DEPTH_A 1
+#endif
+#ifndef MOE_Q4_DEPTH_B
+#define MOE_Q4_DEPTH_B 4
+#endif
+constexpr int kDepthA = MOE_Q4_DEPTH_A;   // gate/up items (2.25 KiB each)
+constexpr int kDepthB = MOE_Q4_DEPTH_B;   // W_d items (1.125 KiB each)
 
 template <typename V>
 __device__ __forceinline__ V ldnt(const void* p) {
@@ -213,7 +223,12 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
   }
 }
 
-int pick_waves_q4(int d) { return d % 512 == 0 ? 8 : d % 256 == 0 ? 4 : 0; }
+int pick_waves_q4(int d) {
+#ifdef MOE_Q4_FORCE_WAVES
+  if (d % (64 * MOE_Q4_FORCE_WAVES) == 0) return MOE_Q4_FORCE_WAVES;
+#endif
+  return d % 512 == 0 ? 8 : d % 256 == 0 ? 4 : 0;
+}
 
 }  // namespace
 

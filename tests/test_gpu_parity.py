@@ -300,6 +300,43 @@ def test_small_bf16_gamma_policy(torch, P, gamma):
     cache.close()
 
 
+@pytest.mark.parametrize("tiled", [False, True])
+@pytest.mark.parametrize("E,K,C", [(1, 1, 1),       # a single expert
+                                   (4, 4, 4),       # every expert selected by every token (K = E)
+                                   (16, 1, 1),      # one slot: every change of expert evicts
+                                   (16, 4, 4),      # capacity = K: a token can evict all of the previous one's
+                                   (16, 4, 100),    # capacity above E is clamped: misses are first touches only
+                                   (64, 8, 63)])    # all but one expert fit
+def test_degenerate_cache_shapes(torch, P, tiled, E, K, C):
+    cfg = small_cfg(n_experts=E, top_k=K, capacity=C, n_layers=1, n_seqs=2, n_steps=20, pref_lo=0, pref_hi=0,
+                    beta=0.0, d_model=256, d_ff=64)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=tiled, trace_capacity=4096)
+    ost = OracleStack(wl, keep=64)
+    _, _, traces = run_sequence_serial(wl, cache, ost, torch=torch, pins=False, y_every=4)
+    st = cache.moe_cache_stats(0)
+    if C >= E:
+        assert st["evictions"] == 0
+    if K == E:
+        assert st["misses"] == E * 2                                  # each sequence starts cold: E first touches
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
+@pytest.mark.parametrize("d_model,d_ff", [(8, 1), (40, 7), (264, 33)])
+def test_odd_widths_take_the_generic_kernels(torch, P, d_model, d_ff):
+    # widths that fit no tile: row-major layout, generic kernels
+    cfg = small_cfg(d_model=d_model, d_ff=d_ff, n_layers=1, n_seqs=2, n_steps=10)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, tiled=False, max_batch=3, staging_buffers=12, trace_capacity=2048)
+    ost = OracleStack(wl)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, [0, 1] if step % 2 else [1], step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_error_paths_on_device(torch, P):
     from paper_2602_11192_amd import binding as B
     cfg = small_cfg(n_layers=1)

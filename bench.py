@@ -285,9 +285,31 @@ def int4_section(torch, P, wl, a):
     rrun.pass_resident()
     n_r, dt_r = timed(torch, rrun.pass_resident, a.steps)
     rcache.close()
+    # a prompt of up to 512 tokens through the stack with the cache read-only: missing experts stream in 4-bit form
+    import numpy as np
+    n_p = min(512, cfg.n_seqs * cfg.n_steps)
+    xp = P.to_device(np.concatenate([wl.tokens(s) for s in range(cfg.n_seqs)])[:n_p])
+    yp = torch.empty((n_p, d), dtype=torch.bfloat16, device="cuda:0")
+    pcache = P.make_cache(wl, int4=True, pool=pool, max_batch=n_p)
+    for l in range(cfg.n_layers):
+        pcache.moe_cache_prefill_pins(l, wl.prefetch_list(l, 0))
+
+    def prompt_pass():
+        for l in range(cfg.n_layers):
+            pcache.moe_layer_prefill(l, xp, yp)
+        return n_p
+
+    prompt_pass()
+    pst0 = pcache.moe_cache_stats()
+    n_pp, dt_pp = timed(torch, prompt_pass, 3)
+    pst = pcache.moe_cache_stats()
+    pcache.close()
     k_bytes = (K + cfg.n_shared) * qb + d * 2 + (K + cfg.n_shared) * d * 4
     k_ms = tm["ffn_fused_ms"] / max(1, tm["ffn_fused_launches"])
-    return {"format": "groups of 32 along the contraction dimension, 4-bit codes + bf16 scale, weight = s * (q - 8)",
+    return {"prompt_streaming": {"prompt_tokens": n_p, "ms_per_layer": dt_pp / 3 / cfg.n_layers * 1e3,
+                                 "tokens_per_s": n_pp / dt_pp,
+                                 "pcie_GBps_lower_bound": (pst["bytes_streamed"] - pst0["bytes_streamed"]) / dt_pp / 1e9},
+            "format": "groups of 32 along the contraction dimension, 4-bit codes + bf16 scale, weight = s * (q - 8)",
             "expert_bytes": qb, "tokens_per_s": n_tok / dt,
             "cache_hit_rate": st["hits"] / max(1, st["lookups"]), "misses_per_token": st["misses"] / max(1, n_tok),
             "pcie_GBps": tm["fetch_bytes"] / (tm["fetch_ms"] * 1e-3) / 1e9 if tm["fetch_ms"] > 0 else None,

@@ -109,8 +109,7 @@ typedef struct {
  *                          (d for W_g, W_u; d_ff for W_d) is stored as 32 codes q in 0..15
  *                          and one bf16 scale s and stands for the weights s * (q - 8);
  *                          4.5 bits per weight.  Written by moe_pack_expert_int4.  x, y and
- *                          the router stay bf16 (dtype = MOE_DTYPE_BF16); decode calls only
- *                          (max_batch <= 16, no moe_layer_prefill); needs d % 256 == 0,
+ *                          the router stay bf16 (dtype = MOE_DTYPE_BF16); needs d % 256 == 0,
  *                          d_ff % 32 == 0.  Statistics count bytes of this block size.
  */
 typedef struct {

@@ -160,8 +160,7 @@ int validate(const moe_cache_config_t* c, const moe_weights_t* w) {
     return fail(MOE_ERR_UNSUPPORTED, "in-kernel fetch needs a tiled layout (bf16 activations)");
   if (c->pool_layout == MOE_LAYOUT_TILED_INT4) {
     if (c->dtype != MOE_DTYPE_BF16) return fail(MOE_ERR_UNSUPPORTED, "INT4 experts need bf16 activations");
-    if (c->max_batch > 16) return fail(MOE_ERR_UNSUPPORTED, "INT4 experts: max_batch must be <= 16 (decode kernel only)");
-    if (!ffn_fused_q4_supported(c->d_model, c->d_ff, c->max_batch))
+    if (!ffn_fused_q4_supported(c->d_model, c->d_ff, 1))
       return fail(MOE_ERR_UNSUPPORTED, "INT4 experts need d_model %% 256 == 0 and d_ff %% 32 == 0");
   }
   if (c->pool_layout == MOE_LAYOUT_TILED) {
@@ -630,7 +629,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   fa.t = c->t; fa.h = c->h; fa.o = c->o;
   const bool tiled = cf.pool_layout == MOE_LAYOUT_TILED;
   const bool q4w = cf.pool_layout == MOE_LAYOUT_TILED_INT4;
-  const bool fused = q4w || (tiled && ffn_fused_supported(d, cf.d_ff, batch));
+  const bool fused = q4w ? batch <= 16 : (tiled && ffn_fused_supported(d, cf.d_ff, batch));
   fa.fused = fused ? 1 : 0;
   // Many tokens per expert: token tiles staged in LDS and shared by the waves of a row block.  Below about 32
   // tokens per expert the split-K streaming kernels are faster (measured); the group sizes are not known to the
@@ -646,7 +645,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   fa.pool = in_kernel ? c->pool_dev + (size_t)layer * E * c->expert_bytes : nullptr;
   fa.fetch = in_kernel ? 1 : 0;
   fa.pass = in_kernel ? 2 : 0;
-  HIPCHK(q4w ? launch_ffn_fused_q4(s, fa, ke1)
+  HIPCHK(q4w ? (fused ? launch_ffn_fused_q4(s, fa, ke1) : launch_ffn_gemm_q4(s, fa, ke1, ke2))
          : fused ? launch_ffn_fused(s, fa, ke1)
          : gemm ? launch_ffn_gemm(s, fa, ke1, ke2)
          : tiled ? launch_ffn_tiled(s, fa, ke1, ke2)
@@ -665,7 +664,8 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
     HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0));
     c->copies_pending = false;
     fa.pass = 1;
-    HIPCHK(q4w ? launch_ffn_fused_q4(s, fa, KernelEvents{})
+    HIPCHK(q4w ? (fused ? launch_ffn_fused_q4(s, fa, KernelEvents{})
+                        : launch_ffn_gemm_q4(s, fa, KernelEvents{}, KernelEvents{}))
            : fused ? launch_ffn_fused(s, fa, KernelEvents{})
            : gemm ? launch_ffn_gemm(s, fa, KernelEvents{}, KernelEvents{})
            : tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
@@ -746,7 +746,7 @@ int moe_layer_prefill(moe_cache_t* c, int32_t layer, const void* x_dev, const fl
   if (n_tokens < 1 || n_tokens > c->cfg.max_batch)
     return fail(MOE_ERR_INVALID_ARG, "n_tokens %d outside 1..max_batch=%d", n_tokens, c->cfg.max_batch);
   if (reinterpret_cast<uintptr_t>(x_dev) & 15) return fail(MOE_ERR_INVALID_ARG, "x_dev must be 16-byte aligned");
-  if (c->cfg.pool_layout != MOE_LAYOUT_TILED) return fail(MOE_ERR_UNSUPPORTED, "prompt streaming needs the tiled bf16 layout");
+  if (c->cfg.pool_layout == MOE_LAYOUT_ROWMAJOR) return fail(MOE_ERR_UNSUPPORTED, "prompt streaming needs a tiled layout");
   if (!c->pool_dev) return fail(MOE_ERR_UNSUPPORTED, "prompt streaming: expert_pool is not device-visible pinned host memory");
   DeviceGuard guard;
   HIPCHK(guard.enter(c->device));
@@ -782,7 +782,8 @@ int moe_layer_prefill(moe_cache_t* c, int32_t layer, const void* x_dev, const fl
   fa.pass = 2; fa.fused = 0;
   fa.pool = c->pool_dev + (size_t)layer * E * c->expert_bytes;
   fa.fetch = 1;
-  HIPCHK(launch_ffn_gemm(s, fa, KernelEvents{}, KernelEvents{}));
+  HIPCHK(cf.pool_layout == MOE_LAYOUT_TILED_INT4 ? launch_ffn_gemm_q4(s, fa, KernelEvents{}, KernelEvents{})
+                                                  : launch_ffn_gemm(s, fa, KernelEvents{}, KernelEvents{}));
 
   HIPCHK(hipEventSynchronize(c->ev_mail));
   const uint32_t got = __atomic_load_n(&c->mailbox->seq, __ATOMIC_ACQUIRE);

@@ -125,6 +125,7 @@ bool ffn_fused_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 bool ffn_fused_q4_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused_q4(hipStream_t s, const FfnArgs& a, KernelEvents ev);
+hipError_t launch_ffn_gemm_q4(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 hipError_t launch_combine_chunks(hipStream_t s, const float* o_part, const float* wpair, const int32_t* pos_of,
                                  int B, int KS, int d, int n_chunks, void* y);
 hipError_t launch_combine(hipStream_t s, int dtype, const float* o, const float* wpair, const int32_t* pos_of,

@@ -64,15 +64,67 @@ def test_int4_batched_with_shared_experts(torch, P, fetch, batch):
 
 def test_int4_limits_are_reported(torch, P):
     from paper_2602_11192_amd import binding as B
-    wl = Workload(small_cfg(d_model=256, d_ff=96))
-    with pytest.raises(B.MoeError):
-        P.make_cache(wl, int4=True, max_batch=17)                      # decode kernel only
     with pytest.raises(B.MoeError):
         P.make_cache(Workload(small_cfg(d_model=128, d_ff=96)), int4=True)      # d_model % 256 != 0
-    cache = P.make_cache(wl, int4=True)
-    x = torch.zeros((4, 256), dtype=torch.bfloat16, device="cuda:0")
-    with pytest.raises(B.MoeError):
-        cache.moe_layer_prefill(0, x, torch.empty_like(x))             # prompt streaming is bf16 only
+    assert B.moe_expert_block_bytes(256, 48, B.MOE_DTYPE_BF16, B.MOE_LAYOUT_TILED_INT4) == 0    # d_ff % 32 != 0
+
+
+@pytest.mark.parametrize("d_model,d_ff", [(256, 96), (512, 160)])
+@pytest.mark.parametrize("batch", [17, 40, 150])
+def test_int4_many_tokens_take_the_grouped_gemm(torch, P, d_model, d_ff, batch):
+    # more than 16 tokens per call: the 4-bit grouped GEMM (up to several token tiles per expert, ragged tails)
+    cfg = small_cfg(d_model=d_model, d_ff=d_ff, n_experts=8, top_k=2, n_seqs=150, n_steps=3, n_layers=1, capacity=8,
+                    n_shared=1, beta=1.0)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, int4=True, max_batch=batch, trace_capacity=4096)
+    ost = OracleStack(wl, int4=True, capacity=8, keep=16)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, list(range(batch)), step))
+    compare_traces_and_stats(cache, ost, traces, q4_bytes(cfg))
+    cache.close()
+
+
+def test_int4_batched_gemm_with_evictions(torch, P):
+    # constrained cache, 24 tokens per call: copy-engine fetches, then the grouped GEMM over the fetched experts
+    cfg = small_cfg(d_model=256, d_ff=96, n_seqs=24, n_steps=5, n_layers=1, capacity=6)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, int4=True, max_batch=24, staging_buffers=10, trace_capacity=8192)
+    ost = OracleStack(wl, int4=True)
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, list(range(24)), step))
+    assert cache.moe_cache_stats(0)["evictions"] > 10
+    compare_traces_and_stats(cache, ost, traces, q4_bytes(cfg))
+    cache.close()
+
+
+@pytest.mark.parametrize("n_tokens", [1, 37, 200])
+def test_int4_prompt_streaming(torch, P, n_tokens):
+    from tests.helpers import TOL, rel_err
+    from workload import widen
+    cfg = small_cfg(n_seqs=2, n_steps=6, n_layers=1, capacity=6, n_shared=1, prefill_len=n_tokens, d_model=256,
+                    d_ff=96)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, int4=True, max_batch=max(n_tokens, 2), trace_capacity=4096)
+    ost = OracleStack(wl, int4=True)
+    pins = wl.prefetch_list(0, 0)[:4]
+    cache.moe_cache_prefill_pins(0, pins)
+    ost.caches[0].pin(pins)
+    xs = wl.prefill_tokens(0)
+    bias = np.tile(wl.bias(0, 0), (n_tokens, 1))
+    y = torch.empty((n_tokens, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.empty((n_tokens, cfg.top_k), dtype=torch.int32, device="cuda:0")
+    for _ in range(2):
+        cache.moe_layer_prefill(0, P.to_device(xs), y, torch.from_numpy(bias).cuda(), idx)
+        res = ost.prefill(0, widen(xs), bias)
+        torch.cuda.synchronize()
+        assert idx.cpu().numpy().tolist() == res.idx.tolist()
+        assert rel_err(P.to_numpy(y), res.y).max() <= TOL["bf16"]
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, [0], step))
+    compare_traces_and_stats(cache, ost, traces, q4_bytes(cfg))
     cache.close()
 
 

@@ -139,3 +139,27 @@ def test_int4_olmoe_like_sampled(torch, P):
     print("int4 olmoe_like worst rel err", worst, "outputs", n_y)
     compare_traces_and_stats(cache, ost, traces, q4_bytes(cfg))
     cache.close()
+
+
+def test_two_caches_interleaved_on_a_side_stream(torch, P):
+    # two independent caches (bf16 with in-kernel fetch, 4-bit with the copy engine) driven alternately on a
+    # non-default stream: no state may leak between them
+    from paper_2602_11192_amd import binding as B
+    cfg_a = small_cfg(cfg_id=21, d_model=256, d_ff=96, n_layers=1, n_seqs=4, n_steps=10, beta=1.0)
+    cfg_b = small_cfg(cfg_id=22, d_model=512, d_ff=64, n_layers=1, n_seqs=4, n_steps=10, capacity=5, n_shared=1)
+    wl_a, wl_b = Workload(cfg_a), Workload(cfg_b)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        cache_a = P.make_cache(wl_a, tiled=True, max_batch=2, staging_buffers=8, trace_capacity=2048,
+                               fetch_mode=B.MOE_FETCH_IN_KERNEL)
+        cache_b = P.make_cache(wl_b, int4=True, max_batch=2, staging_buffers=8, trace_capacity=2048)
+        ost_a, ost_b = OracleStack(wl_a), OracleStack(wl_b, int4=True)
+        tr_a, tr_b = [[]], [[]]
+        for step in range(cfg_a.n_steps):
+            rows = [0, 1] if step % 3 else [2]
+            tr_a[0].extend(batched_step(torch, P, wl_a, cache_a, ost_a, 0, rows, step))
+            tr_b[0].extend(batched_step(torch, P, wl_b, cache_b, ost_b, 0, rows[::-1], step))
+        compare_traces_and_stats(cache_a, ost_a, tr_a, cfg_a.expert_bytes)
+        compare_traces_and_stats(cache_b, ost_b, tr_b, q4_bytes(cfg_b))
+        cache_a.close()
+        cache_b.close()

@@ -608,7 +608,7 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
   // ---- shortcut for a call whose lookups all hit (the resident regime): residency does not change, and the
   //      recency updates commute - the last lookup of a slot decides its tick.  Lookups run 64 per step. ----
   bool all_hit = false;
-  if (a.mode == 0 && f.n_res > 0 && n_lookups >= 16) {     // for a handful of lookups the in-order loop is cheaper
+  if (a.mode == 0 && f.n_res > 0 && n_lookups >= 16) {     // a handful of lookups takes the register variant below
     for (int e = lane; e < a.E; e += kWave) lds_slot_of[e] = -1;
     if (lane < P) { lds_last[lane] = 0; lds_touch[lane] = 0; }
     wave_sync();
@@ -621,7 +621,35 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
     }
     all_hit = any_miss == 0;
   }
-  if (all_hit) {
+  // the same shortcut for a handful of lookups (one per lane), entirely in registers: nothing is changed
+  // unless every lookup hits
+  if (a.mode == 0 && f.n_res > 0 && n_lookups < 16 && small) {
+    const int my_e = lane < n_lookups ? idx_src[lane] : -3;
+    int my_slot = 0;
+    uint64_t new_tick = f.tick;
+    bool ok = true;
+    for (int q = 0; q < n_lookups; ++q) {       // uniform
+      const uint64_t hm = __ballot(f.exp == readlane_i(my_e, q));
+      if (hm == 0) { ok = false; break; }
+      const int s = __ffsll((unsigned long long)hm) - 1;
+      if (lane == q) my_slot = s;
+      if (lane == s) new_tick = (uint64_t)(f.clock + q + 1);    // the last lookup of a slot decides its tick
+    }
+    if (ok) {
+      f.tick = new_tick;
+      const int my_buf = __shfl(f.buf, my_slot);                // lane q: buffer that lookup q reads
+      for (int q = 0; q < n_lookups; ++q)
+        if (lane == readlane_i(my_buf, q)) f.used = seq;
+      if (lane < n_lookups && f.trace_n + lane < a.trace_cap)
+        st.trace[f.trace_n + lane] = moe_trace_rec_t{a.row0 + lane / K, my_e, 1, -1};
+      const int b = lane / KS, k = lane - b * KS;
+      const int v = __shfl(my_buf, k < K ? b * K + k : 0);
+      if (lane < NP && k < K) my_pair = v;
+      f.clock += n_lookups;
+      n_hits = n_lookups;
+      all_hit = true;
+    }
+  } else if (all_hit) {
     for (int chunk0 = 0; chunk0 < n_lookups; chunk0 += kWave) {
       const int l = chunk0 + lane;
       const bool valid = l < n_lookups;

@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--int4", choices=["auto", "on", "off"], default="auto",
                     help="also run the workload with 4-bit group-quantised experts and report it under "
                          "'int4_experts' (auto: only when the whole pool has at most 5e8 weights)")
+    ap.add_argument("--sweep-sizes", default=None, help="comma-separated batch sizes for --batch-sweep")
     ap.add_argument("--extras", metavar="FILE", default=None,
                     help="also measure the widened rows (eviction policies, shared-cache batched decode with pooled "
                          "prefetch, prompt streaming, cache-simulation loss) and write them to FILE (JSON)")
@@ -509,7 +510,8 @@ def main():
         "setup_s": t_gen,
     }
     if a.batch_sweep:
-        json.dump(batch_sweep(torch, P, wl, pool), open(a.batch_sweep, "w"), indent=1)
+        kw = {"sizes": tuple(int(v) for v in a.sweep_sizes.split(","))} if a.sweep_sizes else {}
+        json.dump(batch_sweep(torch, P, wl, pool, **kw), open(a.batch_sweep, "w"), indent=1)
     if a.extras:
         json.dump(extras(torch, P, wl, pool, a), open(a.extras, "w"), indent=1)
     n_weights = cfg.n_layers * cfg.n_experts * 3 * d * f

@@ -77,7 +77,9 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
                   : a.shared + (size_t)(id - a.P) * a.expert_bytes;
 }
 
-template <int WAVES>
+// ONE: every group holds a single token (batch 1).  Only component 0 of the MFMA results (token 0 of the tile) is
+// then scaled and accumulated, which removes a quarter of the vector arithmetic that bounds this kernel.
+template <int WAVES, bool ONE>
 __global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
   __shared__ float red[WAVES][2][256];            // partial gate / up tiles of the waves
   __shared__ __align__(16) uint16_t hs[16][32];   // h of the chunk, bf16, [token][row in chunk]
@@ -158,8 +160,13 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
           const f32x4 off = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, minus136, zero, 0, 0, 0);
           const f32x4 dg = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, codes_to_bf16(awg[u][j]), off, 0, 0, 0);
           const f32x4 du = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, codes_to_bf16(awu[u][j]), off, 0, 0, 0);
-          accg += scale_at(asc[u], j) * dg;
-          accu += scale_at(asc[u], 4 + j) * du;
+          if (ONE) {
+            accg[0] = fmaf(scale_at(asc[u], j), dg[0], accg[0]);
+            accu[0] = fmaf(scale_at(asc[u], 4 + j), du[0], accu[0]);
+          } else {
+            accg += scale_at(asc[u], j) * dg;
+            accu += scale_at(asc[u], 4 + j) * du;
+          }
         }
         if (from_host) {
           const char* rec = pa + (size_t)(base + u) * a_step;
@@ -201,11 +208,13 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
     for (int u = 0; u < kDepthB; ++u) {
       const int j = base + u;
       if (j < nb) {             // uniform
-        f32x4 r[4];
+        f32x4 r[4] = {zero, zero, zero, zero};
 #pragma unroll
-        for (int m = 0; m < 4; ++m)
-          r[m] = scale_at(bsd[u], m) *
-                 __builtin_amdgcn_mfma_f32_16x16x32_bf16(hb, codes_to_bf16(bwd[u][m]), hoff, 0, 0, 0);
+        for (int m = 0; m < 4; ++m) {
+          const f32x4 dd = __builtin_amdgcn_mfma_f32_16x16x32_bf16(hb, codes_to_bf16(bwd[u][m]), hoff, 0, 0, 0);
+          if (ONE) r[m][0] = scale_at(bsd[u], m) * dd[0];
+          else r[m] = scale_at(bsd[u], m) * dd;
+        }
         if (from_host) {
           const char* rec = pb + (size_t)j * b_step;
           fill(rec + lane * 16, bwd[u]);
@@ -214,7 +223,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
         issue_b(u, j + kDepthB);
         const int dq = wave + WAVES * j;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < (ONE ? 1 : 4); ++i)
           if (q * 4 + i < cnt)
             *reinterpret_cast<f32x4*>(obase + (size_t)i * n_chunks * d + (size_t)dq * 64) =
                 f32x4{r[0][i], r[1][i], r[2][i], r[3][i]};
@@ -240,8 +249,14 @@ hipError_t launch_ffn_fused_q4(hipStream_t s, const FfnArgs& a, KernelEvents ev)
   if (a.g_max <= 0) return hipSuccess;
   dim3 grid(a.f / 32, a.g_max);
   switch (pick_waves_q4(a.d)) {
-    case 8: launch_timed(ffn_fused_q4_kernel<8>, grid, dim3(512), 0, s, ev, a); break;
-    case 4: launch_timed(ffn_fused_q4_kernel<4>, grid, dim3(256), 0, s, ev, a); break;
+    case 8:
+      if (a.max_count == 1) launch_timed(ffn_fused_q4_kernel<8, true>, grid, dim3(512), 0, s, ev, a);
+      else launch_timed(ffn_fused_q4_kernel<8, false>, grid, dim3(512), 0, s, ev, a);
+      break;
+    case 4:
+      if (a.max_count == 1) launch_timed(ffn_fused_q4_kernel<4, true>, grid, dim3(256), 0, s, ev, a);
+      else launch_timed(ffn_fused_q4_kernel<4, false>, grid, dim3(256), 0, s, ev, a);
+      break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -337,6 +337,33 @@ def test_odd_widths_take_the_generic_kernels(torch, P, d_model, d_ff):
     cache.close()
 
 
+@pytest.mark.parametrize("E,K,C,n_shared,batch,policy", [
+    (16, 4, 16, 1, 130, "lru"),      # everything resident: parallel all-hit path, shared expert
+    (16, 4, 6, 0, 128, "lru"),       # constrained: misses inside the call, in-order routine, waves of tokens
+    (8, 2, 8, 0, 300, "lru"),        # fewer experts than one tile of 16
+    (100, 6, 100, 0, 200, "lru"),    # 64 < E <= 256, table larger than a wave (LDS table)
+    (64, 8, 64, 2, 144, "lru"),      # 64 slots, 64 buffers, shared experts
+    (16, 4, 8, 0, 140, "gamma"),     # discounted-count policy
+])
+def test_large_calls_route_in_tiles_of_16_tokens(torch, P, E, K, C, n_shared, batch, policy):
+    # calls of 128 tokens and more: router logits of 16 tokens per workgroup on the matrix cores, cache phase on
+    # four waves; routing, traces and outputs must not depend on which kernel ran
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(n_experts=E, top_k=K, capacity=C, n_shared=n_shared, n_seqs=batch, n_steps=3, n_layers=1,
+                    d_model=256, d_ff=64, beta=1.0, pref_lo=min(4, K), pref_hi=min(4, K))
+    wl = Workload(cfg)
+    kw = dict(policy=B.MOE_POLICY_GAMMA, gamma=0.9) if policy == "gamma" else {}
+    cache = P.make_cache(wl, tiled=True, max_batch=batch, staging_buffers=max(0, min(E, 64) - C), trace_capacity=1 << 15,
+                         **kw)
+    ost = OracleStack(wl, keep=128, **(dict(policy=oracle.POLICY_GAMMA, gamma=0.9) if policy == "gamma" else {}))
+    traces = [[]]
+    for step in range(cfg.n_steps):
+        rows = list(range(batch)) if step != 1 else list(range(3))          # a small call in between
+        traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, rows, step))
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_error_paths_on_device(torch, P):
     from paper_2602_11192_amd import binding as B
     cfg = small_cfg(n_layers=1)

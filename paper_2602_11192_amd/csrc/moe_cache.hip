@@ -631,11 +631,10 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   const bool q4w = cf.pool_layout == MOE_LAYOUT_TILED_INT4;
   const bool fused = q4w ? batch <= 16 : (tiled && ffn_fused_supported(d, cf.d_ff, batch));
   fa.fused = fused ? 1 : 0;
-  // Many tokens per expert: token tiles staged in LDS and shared by the waves of a row block.  Below about 32
-  // tokens per expert the split-K streaming kernels are faster (measured); the group sizes are not known to the
-  // host at launch, so the expected load batch * K / (experts that can be in use) decides.
-  const int experts_in_use = std::min(E, c->P);
-  const bool gemm = tiled && !fused && (int64_t)batch * K > (int64_t)24 * experts_in_use;
+  // More than 16 tokens per call: the LDS-staged grouped GEMM (measured faster than the split-K streaming pair
+  // from 17 tokens on: 119 against 139 us at 17 tokens, 138 against 190 us at 128 on the OLMoE-like layer).  The
+  // split-K pair remains for small calls on shapes the single-launch kernel does not cover.
+  const bool gemm = tiled && !fused && batch > 16;
   const KernelEvents ke1 = ps ? ps->gate_up : KernelEvents{}, ke2 = ps ? ps->down : KernelEvents{};
 
   // Experts that were already resident: their FFN starts right behind the cache

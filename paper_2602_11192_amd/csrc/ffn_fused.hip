@@ -1,6 +1,7 @@
 // Decode-shape expert FFN (paper section 2, Eq. 3) in ONE launch: gate/up
 // projection, SiLU * up, and the down projection, for groups of at most 16
-// tokens per expert (batch <= 16), on bf16 experts in the tiled layout.
+// tokens per expert, on bf16 experts in the tiled layout (the host uses it for calls of up to 8 tokens; the grouped
+// GEMM is faster beyond).
 //
 // Why one launch: at decode an expert sees one or a few tokens, every weight
 // byte is used once, and a whole layer call moves only ~100 MB - about 13 us of
@@ -261,7 +262,7 @@ void launch_fused_waves(hipStream_t s, const FfnArgs& a, KernelEvents ev) {
 }  // namespace
 
 bool ffn_fused_supported(int d, int f, int max_count) {
-  return max_count <= 16 && f % 32 == 0 && pick_waves(d, 1) != 0;
+  return max_count <= kFusedMaxTokens && f % 32 == 0 && pick_waves(d, 1) != 0;
 }
 
 hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev) {

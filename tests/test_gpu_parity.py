@@ -107,10 +107,10 @@ def test_small_bf16_batched_with_evictions_inside_a_call(torch, P, tiled, batch)
 
 
 @pytest.mark.parametrize("d_model,d_ff", [(256, 96), (512, 160), (1024, 64)])
-@pytest.mark.parametrize("batch", [1, 4, 16, 17])
+@pytest.mark.parametrize("batch", [1, 4, 8, 9, 16, 17])
 def test_single_launch_decode_ffn_shapes(torch, P, d_model, d_ff, batch):
-    # hidden widths that are multiples of 256 take the single-launch decode FFN for calls of up to 16 tokens;
-    # 17 tokens fall back to the two-kernel path on the same cache
+    # hidden widths that are multiples of 256 take the single-launch decode FFN for calls of up to 8 tokens;
+    # larger calls take the grouped GEMM on the same cache
     cfg = small_cfg(d_model=d_model, d_ff=d_ff, n_seqs=17, n_steps=4, n_layers=1, capacity=16, n_shared=1)
     wl = Workload(cfg)
     cache = P.make_cache(wl, tiled=True, max_batch=17, trace_capacity=4096)

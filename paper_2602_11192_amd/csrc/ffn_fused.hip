@@ -1,6 +1,6 @@
 // Decode-shape expert FFN (paper section 2, Eq. 3) in ONE launch: gate/up
 // projection, SiLU * up, and the down projection, for groups of at most 16
-// tokens per expert, on bf16 experts in the tiled layout (the host uses it for calls of up to 8 tokens; the grouped
+// tokens per expert, on bf16 experts in the tiled layout (the host uses it for calls of up to 6 tokens; the grouped
 // GEMM is faster beyond).
 //
 // Why one launch: at decode an expert sees one or a few tokens, every weight

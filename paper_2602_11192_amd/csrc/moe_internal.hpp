@@ -121,9 +121,10 @@ hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P
 hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
-// Most tokens per call for which the single-launch bf16 decode kernel is used (it can take 16 per expert; beyond
-// 8 the grouped GEMM is faster).
-constexpr int kFusedMaxTokens = 8;
+// Most tokens per call for which the single-launch bf16 decode kernel is used (it can take 16 per expert; the
+// whole call is faster with the grouped GEMM from about 6 tokens on: 109 against 110 us at 6, 119 against 133 us
+// at 8 on the OLMoE-like layer).
+constexpr int kFusedMaxTokens = 6;
 bool ffn_fused_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 bool ffn_fused_q4_supported(int d, int f, int max_count);

@@ -107,9 +107,9 @@ def test_small_bf16_batched_with_evictions_inside_a_call(torch, P, tiled, batch)
 
 
 @pytest.mark.parametrize("d_model,d_ff", [(256, 96), (512, 160), (1024, 64)])
-@pytest.mark.parametrize("batch", [1, 4, 8, 9, 16, 17])
+@pytest.mark.parametrize("batch", [1, 4, 6, 7, 16, 17])
 def test_single_launch_decode_ffn_shapes(torch, P, d_model, d_ff, batch):
-    # hidden widths that are multiples of 256 take the single-launch decode FFN for calls of up to 8 tokens;
+    # hidden widths that are multiples of 256 take the single-launch decode FFN for calls of up to 6 tokens;
     # larger calls take the grouped GEMM on the same cache
     cfg = small_cfg(d_model=d_model, d_ff=d_ff, n_seqs=17, n_steps=4, n_layers=1, capacity=16, n_shared=1)
     wl = Workload(cfg)
@@ -122,7 +122,7 @@ def test_single_launch_decode_ffn_shapes(torch, P, d_model, d_ff, batch):
     cache.close()
 
 
-@pytest.mark.parametrize("batch", [1, 3, 7])
+@pytest.mark.parametrize("batch", [1, 3, 5, 7])
 def test_in_kernel_fetch_matches_oracle(torch, P, batch):
     # missed experts are read from the pinned pool by the expert kernel itself and land in their buffers
     from paper_2602_11192_amd import binding as B

@@ -391,7 +391,9 @@ def main():
         cfg = cfg.with_(n_steps=a.decode_steps)
     wl = Workload(cfg)
     t0 = time.perf_counter()
-    pool = P.build_pool(wl, tiled=True)
+    # pools beyond 40 GB are pinned layer by layer (one allocation of the whole stack can be refused)
+    per_layer = cfg.n_layers * cfg.n_experts * cfg.expert_bytes > 40e9
+    pool = P.build_pool(wl, tiled=True, per_layer=per_layer)
     for s in range(cfg.n_seqs):
         wl.tokens(s)
     t_gen = time.perf_counter() - t0

@@ -114,8 +114,13 @@ typedef struct {
  */
 typedef struct {
   const void* router_w;    /* device, [L][E][d] row-major, dtype                            */
-  const void* expert_pool; /* pinned host, [L][E] expert blocks                             */
+  const void* expert_pool; /* pinned host, [L][E] expert blocks in one allocation; or NULL  */
   const void* shared_w;    /* device, [L][n_shared] expert blocks; NULL iff n_shared == 0   */
+  const void* const* expert_pool_layers; /* or: host array of L pointers, each to one layer's
+                              [E] expert blocks in pinned host memory (for stacks whose pool
+                              is too large to pin in one piece); the array itself is read
+                              only during moe_cache_create.  Exactly one of expert_pool and
+                              expert_pool_layers is non-NULL                                */
 } moe_weights_t;
 
 typedef struct {

@@ -42,7 +42,8 @@ class moe_cache_config_t(C.Structure):
 
 
 class moe_weights_t(C.Structure):
-    _fields_ = [("router_w", C.c_void_p), ("expert_pool", C.c_void_p), ("shared_w", C.c_void_p)]
+    _fields_ = [("router_w", C.c_void_p), ("expert_pool", C.c_void_p), ("shared_w", C.c_void_p),
+                ("expert_pool_layers", C.POINTER(C.c_void_p))]
 
 
 class moe_cache_stats_t(C.Structure):
@@ -203,7 +204,11 @@ class MoECache:
                                       norm_topk, policy, max_batch, staging_buffers, device_id, trace_capacity,
                                       pool_layout, fetch_mode, float(gamma))
         self._keep = (router_w, expert_pool, shared_w)
-        w = moe_weights_t(_ptr(router_w), _ptr(expert_pool), _ptr(shared_w))
+        if isinstance(expert_pool, (list, tuple)):         # one pinned tensor per layer
+            arr = (C.c_void_p * len(expert_pool))(*[p.data_ptr() for p in expert_pool])
+            w = moe_weights_t(_ptr(router_w), None, _ptr(shared_w), arr)
+        else:
+            w = moe_weights_t(_ptr(router_w), _ptr(expert_pool), _ptr(shared_w), None)
         self._h = C.c_void_p()
         _check(lib.moe_cache_create(C.byref(self.cfg), C.byref(w), C.byref(self._h)))
 

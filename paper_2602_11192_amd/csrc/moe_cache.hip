@@ -82,7 +82,8 @@ struct moe_cache {
   float* o = nullptr;
   int32_t* arrive = nullptr;
   uint64_t wave_splits = 0;         // calls that had to be run as two waves of tokens
-  const char* pool_dev = nullptr;   // the pinned pool as the device sees it (in-kernel fetch)
+  std::vector<const char*> pool_host;  // [L] each layer's E expert blocks in pinned host memory
+  std::vector<const char*> pool_dev;   // [L] the same as the device sees it (in-kernel fetch); empty if not mapped
 
   char* host_mem = nullptr;       // pinned: mailbox | pin ids | miss list
   Mailbox* mailbox = nullptr;
@@ -150,7 +151,13 @@ int validate(const moe_cache_config_t* c, const moe_weights_t* w) {
   if (c->capacity < c->top_k)
     return fail(MOE_ERR_CAPACITY_LT_TOPK, "capacity %d < top_k %d: one token's experts would not fit", c->capacity,
                 c->top_k);
-  if (!w->router_w || !w->expert_pool) return fail(MOE_ERR_INVALID_ARG, "router_w and expert_pool must not be null");
+  if (!w->router_w) return fail(MOE_ERR_INVALID_ARG, "router_w must not be null");
+  if ((w->expert_pool != nullptr) == (w->expert_pool_layers != nullptr))
+    return fail(MOE_ERR_INVALID_ARG, "exactly one of expert_pool and expert_pool_layers must be given");
+  if (w->expert_pool_layers)
+    for (int l = 0; l < c->n_layers; ++l)
+      if (!w->expert_pool_layers[l] || (reinterpret_cast<uintptr_t>(w->expert_pool_layers[l]) & 15))
+        return fail(MOE_ERR_INVALID_ARG, "expert_pool_layers[%d] is null or not 16-byte aligned", l);
   if ((c->n_shared > 0) != (w->shared_w != nullptr))
     return fail(MOE_ERR_INVALID_ARG, "shared_w must be given exactly when n_shared > 0");
   const int vec = c->dtype == MOE_DTYPE_FP32 ? 4 : 8;
@@ -210,7 +217,7 @@ int wait_mailbox(moe_cache* c, hipStream_t s, uint32_t seq) {
 // Issue the expert copies of the current mailbox on the copy stream.
 int issue_copies(moe_cache* c, int layer, int n) {
   const size_t eb = c->expert_bytes;
-  const char* pool = static_cast<const char*>(c->w.expert_pool) + (size_t)layer * c->cfg.n_experts * eb;
+  const char* pool = c->pool_host[layer];
   char* bufs = c->buffers + (size_t)layer * c->P * eb;
   CopySlot* cs = nullptr;
   if (c->profiling) {
@@ -493,11 +500,30 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->miss_list = reinterpret_cast<MissEntry*>(c->host_mem + align_up(sizeof(Mailbox), 64) + align_up((size_t)C * 4, 64));
 
   {
-    // the pinned pool as the device sees it (in-kernel fetch, prompt streaming); absent for pageable memory
-    void* dp = nullptr;
-    hipError_t e_ = hipHostGetDevicePointer(&dp, const_cast<void*>(weights->expert_pool), 0);
-    if (e_ == hipSuccess && dp != nullptr) {
-      c->pool_dev = static_cast<const char*>(dp);
+    c->pool_host.resize(L);
+    for (int l = 0; l < L; ++l)
+      c->pool_host[l] = weights->expert_pool_layers
+                            ? static_cast<const char*>(weights->expert_pool_layers[l])
+                            : static_cast<const char*>(weights->expert_pool) + (size_t)l * E * c->expert_bytes;
+    // the device's view of the pinned pool(s); without it only the copy engine can fetch
+    std::vector<const char*> dev(L);
+    bool mapped = true;
+    hipError_t e_ = hipSuccess;
+    if (weights->expert_pool_layers) {
+      for (int l = 0; l < L && mapped; ++l) {
+        void* dp = nullptr;
+        e_ = hipHostGetDevicePointer(&dp, const_cast<char*>(c->pool_host[l]), 0);
+        mapped = e_ == hipSuccess && dp != nullptr;
+        dev[l] = static_cast<const char*>(dp);
+      }
+    } else {
+      void* dp = nullptr;
+      e_ = hipHostGetDevicePointer(&dp, const_cast<void*>(weights->expert_pool), 0);
+      mapped = e_ == hipSuccess && dp != nullptr;
+      for (int l = 0; l < L && mapped; ++l) dev[l] = static_cast<const char*>(dp) + (size_t)l * E * c->expert_bytes;
+    }
+    if (mapped) {
+      c->pool_dev = dev;
     } else {
       (void)hipGetLastError();
       if (cfg->fetch_mode == MOE_FETCH_IN_KERNEL) {
@@ -642,7 +668,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   // lookups, before the host knows the miss list.  With in-kernel fetch the same
   // launch also streams the missed experts from the host pool.
   const bool in_kernel = fused && cf.fetch_mode == MOE_FETCH_IN_KERNEL;
-  fa.pool = in_kernel ? c->pool_dev + (size_t)layer * E * c->expert_bytes : nullptr;
+  fa.pool = in_kernel ? c->pool_dev[layer] : nullptr;
   fa.fetch = in_kernel ? 1 : 0;
   fa.pass = in_kernel ? 2 : 0;
   HIPCHK(q4w ? (fused ? launch_ffn_fused_q4(s, fa, ke1) : launch_ffn_gemm_q4(s, fa, ke1, ke2))
@@ -747,7 +773,7 @@ int moe_layer_prefill(moe_cache_t* c, int32_t layer, const void* x_dev, const fl
     return fail(MOE_ERR_INVALID_ARG, "n_tokens %d outside 1..max_batch=%d", n_tokens, c->cfg.max_batch);
   if (reinterpret_cast<uintptr_t>(x_dev) & 15) return fail(MOE_ERR_INVALID_ARG, "x_dev must be 16-byte aligned");
   if (c->cfg.pool_layout == MOE_LAYOUT_ROWMAJOR) return fail(MOE_ERR_UNSUPPORTED, "prompt streaming needs a tiled layout");
-  if (!c->pool_dev) return fail(MOE_ERR_UNSUPPORTED, "prompt streaming: expert_pool is not device-visible pinned host memory");
+  if (c->pool_dev.empty()) return fail(MOE_ERR_UNSUPPORTED, "prompt streaming: expert_pool is not device-visible pinned host memory");
   DeviceGuard guard;
   HIPCHK(guard.enter(c->device));
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -780,7 +806,7 @@ int moe_layer_prefill(moe_cache_t* c, int32_t layer, const void* x_dev, const fl
   fa.max_count = n_tokens;
   fa.t = c->t; fa.h = c->h; fa.o = c->o;
   fa.pass = 2; fa.fused = 0;
-  fa.pool = c->pool_dev + (size_t)layer * E * c->expert_bytes;
+  fa.pool = c->pool_dev[layer];
   fa.fetch = 1;
   HIPCHK(cf.pool_layout == MOE_LAYOUT_TILED_INT4 ? launch_ffn_gemm_q4(s, fa, KernelEvents{}, KernelEvents{})
                                                   : launch_ffn_gemm(s, fa, KernelEvents{}, KernelEvents{}));

@@ -53,8 +53,11 @@ def _block_int4(quantised, cfg) -> np.ndarray:
     return out
 
 
-def build_pool(wl, tiled: bool, workers: int = 8, int4: bool = False) -> torch.Tensor:
-    """Pinned host tensor [L][E] expert blocks (flat), storage dtype (uint8 for 4-bit experts)."""
+def build_pool(wl, tiled: bool, workers: int = 8, int4: bool = False, per_layer: bool = False):
+    """Pinned host tensor [L][E] expert blocks (flat), storage dtype (uint8 for 4-bit experts); per_layer: a list
+    of L such tensors of [E] blocks each, for stacks too large to pin in one allocation."""
+    if per_layer:
+        return [build_pool(_LayerView(wl, l), tiled, workers, int4) for l in range(wl.cfg.n_layers)]
     cfg = wl.cfg
     n = cfg.n_layers * cfg.n_experts
     if int4:
@@ -77,6 +80,20 @@ def build_pool(wl, tiled: bool, workers: int = 8, int4: bool = False) -> torch.T
     with ThreadPoolExecutor(max_workers=workers) as ex:
         list(ex.map(fill, range(n)))
     return pool
+
+
+class _LayerView:
+    """One layer of a workload, seen as a single-layer workload (for building per-layer pools)."""
+
+    def __init__(self, wl, layer):
+        self._wl, self._layer = wl, layer
+        self.cfg = wl.cfg.with_(n_layers=1)
+
+    def expert(self, l, e):
+        return self._wl.expert(self._layer, e)
+
+    def expert_int4(self, l, e):
+        return self._wl.expert_int4(self._layer, e)
 
 
 def build_router(wl, device="cuda:0") -> torch.Tensor:

@@ -36,7 +36,7 @@ def test_struct_sizes_match_header(B):
     assert C.sizeof(B.moe_cache_config_t) == 16 * 4 + 8
     assert C.sizeof(B.moe_cache_stats_t) == 64
     assert C.sizeof(B.moe_trace_rec_t) == 16
-    assert C.sizeof(B.moe_weights_t) == 24
+    assert C.sizeof(B.moe_weights_t) == 32
 
 
 def test_expert_bytes(B):

@@ -364,6 +364,23 @@ def test_large_calls_route_in_tiles_of_16_tokens(torch, P, E, K, C, n_shared, ba
     cache.close()
 
 
+@pytest.mark.parametrize("fetch", ["copy_engine", "in_kernel"])
+def test_one_pinned_pool_per_layer(torch, P, fetch):
+    # the expert pool handed over as L separate pinned allocations (expert_pool_layers)
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(n_layers=3, n_seqs=2, n_steps=12, d_model=256, d_ff=96, beta=1.0)
+    wl = Workload(cfg)
+    pools = P.build_pool(wl, tiled=True, per_layer=True)
+    assert isinstance(pools, list) and len(pools) == 3
+    cache = P.make_cache(wl, tiled=True, pool=pools, trace_capacity=4096,
+                         fetch_mode=B.MOE_FETCH_IN_KERNEL if fetch == "in_kernel" else B.MOE_FETCH_COPY_ENGINE)
+    ost = OracleStack(wl)
+    _, _, traces = run_sequence_serial(wl, cache, ost, torch=torch)
+    assert cache.moe_cache_stats()["misses"] > 10
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    cache.close()
+
+
 def test_error_paths_on_device(torch, P):
     from paper_2602_11192_amd import binding as B
     cfg = small_cfg(n_layers=1)

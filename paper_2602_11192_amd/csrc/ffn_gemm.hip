@@ -188,7 +188,8 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
 hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, KernelEvents e2) {
   if (a.g_max <= 0) return hipSuccess;
   // the group sizes are not known on the host; the mean load decides the token tile
-  const bool small_tile = (int64_t)a.max_count * a.KS <= (int64_t)64 * a.g_max;
+  // (experts streamed from the host are read once per token tile: the large tile keeps that to one read up to 128 tokens)
+  const bool small_tile = a.fetch == 0 && (int64_t)a.max_count * a.KS <= (int64_t)64 * a.g_max;
   const int tok_tile = small_tile ? 64 : 128;
   const int tiles = (a.max_count + tok_tile - 1) / tok_tile;
   dim3 block(64 * kGemmWaves);

@@ -30,8 +30,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWaves = 4;
-constexpr int kTok = 64;            // tokens per workgroup
-constexpr int kCb = kTok / 16;      // column blocks of 16 tokens
 constexpr int kSkb = 4;             // k-blocks staged per step
 
 template <typename V>
@@ -59,8 +57,12 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
                   : a.shared + (size_t)(id - a.P) * a.expert_bytes;
 }
 
-template <int NMAT>
+// kTok: tokens per workgroup (64 or 128).  An expert streamed from the host is read once per token tile, so prompt
+// streaming takes the large tile; the small one needs half the accumulators.
+template <int NMAT, int kTok>
 __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
+  constexpr int kCb = kTok / 16;      // column blocks of 16 tokens
+  constexpr int kPieces = kTok / 16;  // 16-byte pieces of the token tile each thread stages per step
   // [buffer][k-block of the step][column block][lane] x 16 bytes
   __shared__ u32x4 xs[2][kSkb][kCb][64];
   const int g = blockIdx.y;
@@ -91,11 +93,11 @@ __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
   const char* wrec = NMAT == 2 ? wsrc + (size_t)uc * nsb * q4::kGateUpRecord
                                : wsrc + q4::gate_up_bytes(d, f) + (size_t)uc * q4::kDownRecord;
 
-  // ---- token staging: 256 threads x 4 pieces of 16 bytes = 64 rows x 256 bytes (4 k-blocks) ----
-  const uint16_t* src[4];
-  int dst[4];
+  // ---- token staging: 256 threads x kPieces pieces of 16 bytes = kTok rows x 256 bytes (4 k-blocks) ----
+  const uint16_t* src[kPieces];
+  int dst[kPieces];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < kPieces; ++i) {
     const int idx = threadIdx.x + 256 * i;
     const int r = idx >> 4, sg = idx & 15;                     // token row of the tile, 16-byte segment of its 256 bytes
     const int kbl = sg >> 2, qq = sg & 3;
@@ -111,9 +113,9 @@ __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
       src[i] = nullptr;
     }
   }
-  auto load_x = [&](u32x4 (&xr)[4], int kb) {
+  auto load_x = [&](u32x4 (&xr)[kPieces], int kb) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < kPieces; ++i) {
       const int kbi = kb + ((threadIdx.x + 256 * i) & 15) / 4;   // k-block this piece belongs to
       xr[i] = (src[i] != nullptr && kbi < nkb) ? *reinterpret_cast<const u32x4*>(src[i] + (size_t)kb * 32)
                                                 : u32x4{0, 0, 0, 0};
@@ -151,11 +153,11 @@ __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
 #pragma unroll
     for (int m = 0; m < NA; ++m) acc[cb][m] = zero;
 
-  u32x4 xr[4], wc[NW], wn[NW];
+  u32x4 xr[kPieces], wc[NW], wn[NW];
   load_x(xr, 0);
   load_w(wc, 0);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) (&xs[0][0][0][0])[dst[i]] = xr[i];
+  for (int i = 0; i < kPieces; ++i) (&xs[0][0][0][0])[dst[i]] = xr[i];
   __syncthreads();
 
   int buf = 0;
@@ -196,7 +198,7 @@ __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
     }
     if (more) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) (&xs[buf ^ 1][0][0][0])[dst[i]] = xr[i];
+      for (int i = 0; i < kPieces; ++i) (&xs[buf ^ 1][0][0][0])[dst[i]] = xr[i];
 #pragma unroll
       for (int m = 0; m < NW; ++m) wc[m] = wn[m];
     }
@@ -230,12 +232,19 @@ __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
 
 hipError_t launch_ffn_gemm_q4(hipStream_t s, const FfnArgs& a, KernelEvents e1, KernelEvents e2) {
   if (a.g_max <= 0) return hipSuccess;
-  const int tiles = (a.max_count + kTok - 1) / kTok;
+  const bool large_tile = a.fetch != 0 || (int64_t)a.max_count * a.KS > (int64_t)64 * a.g_max;
+  const int tok = large_tile ? 128 : 64;
+  const int tiles = (a.max_count + tok - 1) / tok;
   dim3 block(64 * kWaves);
   dim3 g1((a.f / 16 + kWaves - 1) / kWaves, a.g_max, tiles);
   dim3 g2((a.d / 64 + kWaves - 1) / kWaves, a.g_max, tiles);
-  launch_timed(ffn_gemm_q4_kernel<2>, g1, block, 0, s, e1, a);
-  launch_timed(ffn_gemm_q4_kernel<1>, g2, block, 0, s, e2, a);
+  if (large_tile) {
+    launch_timed(ffn_gemm_q4_kernel<2, 128>, g1, block, 0, s, e1, a);
+    launch_timed(ffn_gemm_q4_kernel<1, 128>, g2, block, 0, s, e2, a);
+  } else {
+    launch_timed(ffn_gemm_q4_kernel<2, 64>, g1, block, 0, s, e1, a);
+    launch_timed(ffn_gemm_q4_kernel<1, 64>, g2, block, 0, s, e2, a);
+  }
   return hipGetLastError();
 }
 

@@ -182,44 +182,53 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
 }
 
 // y[b][i] = sum_j wpair[b][j] * sum_c o_part[pos_of[b][j]][c][i].
-// A workgroup owns 16 columns of one token; its 64 slices split the KS * n_chunks
-// terms (every load issued before the first use), then the slices are summed in
-// slice order: the result does not depend on timing.
-constexpr int kCombCols = 16, kCombSlices = 64, kCombItems = 16;
+// A workgroup owns 32 columns (128 bytes of every partial row) of one token: 8 lanes x 4 columns, 128 slices.
+// The slices split the KS * n_chunks partial rows; a thread reads 16 bytes per row, all loads of a batch issued
+// before the first use.  The slices are then summed in a fixed order (butterfly inside the wave, wave order in
+// LDS), so the result does not depend on timing.
+constexpr int kCombLanes = 8, kCombSlices = 128, kCombBatch = 8;
 
 template <typename T>
-__global__ void __launch_bounds__(kCombCols * kCombSlices)
+__global__ void __launch_bounds__(kCombLanes * kCombSlices)
 combine_chunks_kernel(const float* __restrict__ o_part, const float* __restrict__ wpair,
                       const int32_t* __restrict__ pos_of, int KS, int d, int n_chunks, T* __restrict__ y) {
-  __shared__ float part[kCombSlices][kCombCols];
+  __shared__ f32x4 part[kCombSlices / 8][kCombLanes];
   const int b = blockIdx.x;
-  const int col = threadIdx.x % kCombCols, sl = threadIdx.x / kCombCols;
-  const int i = blockIdx.y * kCombCols + col;
+  const int cl = threadIdx.x % kCombLanes, sl = threadIdx.x / kCombLanes;
+  const int col = blockIdx.y * (kCombLanes * 4) + cl * 4;       // host guarantees d % 32 == 0
   const int n_items = KS * n_chunks;
   const int per = (n_items + kCombSlices - 1) / kCombSlices;
-  float acc = 0.f;
-  if (i < d) {
-    for (int it0 = sl * per; it0 < min((sl + 1) * per, n_items); it0 += kCombItems) {
-      float v[kCombItems], w[kCombItems];
+  const int it_end = min((sl + 1) * per, n_items);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int it0 = sl * per; it0 < it_end; it0 += kCombBatch) {
+    f32x4 v[kCombBatch];
+    float w[kCombBatch];
 #pragma unroll
-      for (int u = 0; u < kCombItems; ++u) {
-        const int it = it0 + u;
-        const bool ok = it < min((sl + 1) * per, n_items);
-        const int j = ok ? it / n_chunks : 0, c = ok ? it - j * n_chunks : 0;
-        w[u] = ok ? wpair[(size_t)b * KS + j] : 0.f;
-        v[u] = o_part[((size_t)pos_of[(size_t)b * KS + j] * n_chunks + c) * d + i];
-      }
-#pragma unroll
-      for (int u = 0; u < kCombItems; ++u) acc = fmaf(w[u], v[u], acc);
+    for (int u = 0; u < kCombBatch; ++u) {
+      const int it = it0 + u;
+      const bool ok = it < it_end;
+      const int j = ok ? it / n_chunks : 0, c = ok ? it - j * n_chunks : 0;
+      w[u] = ok ? wpair[(size_t)b * KS + j] : 0.f;
+      v[u] = *reinterpret_cast<const f32x4*>(o_part + ((size_t)pos_of[(size_t)b * KS + j] * n_chunks + c) * d + col);
     }
-  }
-  part[sl][col] = acc;
-  __syncthreads();
-  if (sl == 0 && i < d) {
-    float s = 0.f;
 #pragma unroll
-    for (int k = 0; k < kCombSlices; ++k) s += part[k][col];
-    Elem<T>::store(y + (size_t)b * d + i, s);
+    for (int u = 0; u < kCombBatch; ++u) acc += w[u] * v[u];
+  }
+  // the 8 slices of a wave (lane bits 3..5), then the 16 waves
+#pragma unroll
+  for (int m = 8; m < 64; m <<= 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] += __shfl_xor(acc[i], m);
+  }
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (lane < kCombLanes) part[wave][lane] = acc;
+  __syncthreads();
+  if (threadIdx.x < kCombLanes) {
+    f32x4 sum = part[0][threadIdx.x];
+#pragma unroll
+    for (int k = 1; k < kCombSlices / 8; ++k) sum += part[k][threadIdx.x];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Elem<T>::store(y + (size_t)b * d + col + i, sum[i]);
   }
 }
 
@@ -279,7 +288,7 @@ hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev) {
 
 hipError_t launch_combine_chunks(hipStream_t s, const float* o_part, const float* wpair, const int32_t* pos_of,
                                  int B, int KS, int d, int n_chunks, void* y) {
-  dim3 grid(B, (d + kCombCols - 1) / kCombCols), block(kCombCols * kCombSlices);
+  dim3 grid(B, d / (kCombLanes * 4)), block(kCombLanes * kCombSlices);
   hipLaunchKernelGGL(combine_chunks_kernel<uint16_t>, grid, block, 0, s, o_part, wpair, pos_of, KS, d, n_chunks,
                      (uint16_t*)y);
   return hipGetLastError();

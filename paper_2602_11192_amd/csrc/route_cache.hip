@@ -814,7 +814,8 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
 }
 
 // ---------------------------------------------------------------- the decode launch
-template <typename T>
+// EB: router rows a wave handles at a time (1 when there are at least as many waves as experts: no spare loads).
+template <typename T, int EB>
 __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerState st, CallTables t, CacheCallArgs a) {
   extern __shared__ __align__(8) unsigned char smem[];
   __shared__ int s_last;
@@ -837,10 +838,9 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
   int32_t* idx_stage = stage ? reinterpret_cast<int32_t*>(smem + L.idx_stage) : nullptr;
   int32_t* pair_stage = stage ? reinterpret_cast<int32_t*>(smem + L.pair_stage) : t.pair_buf;
 
-  // ---- phase 1: router rows of token b, four rows per wave at a time ----
+  // ---- phase 1: router rows of token b, EB rows per wave at a time ----
   {
     using V = Vec<T>;
-    constexpr int EB = 4;
     const int n_vec = d / V::N;  // host guarantees d % V::N == 0
     const typename V::type* xv = reinterpret_cast<const typename V::type*>(static_cast<const T*>(r.x) + (size_t)b * d);
     const typename V::type* wbase = reinterpret_cast<const typename V::type*>(r.router_w);
@@ -851,7 +851,9 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
         const int e = e0 + j * n_waves;
         wv[j] = wbase + (size_t)(e < E ? e : E - 1) * n_vec;   // clamped: loads stay unconditional
       }
-      float acc[EB] = {0.f, 0.f, 0.f, 0.f};
+      float acc[EB];
+#pragma unroll
+      for (int j = 0; j < EB; ++j) acc[j] = 0.f;
       constexpr int CB = 4;   // chunks per lane fetched together: (1 + EB) * CB loads in flight
       for (int c0 = lane; c0 < n_vec; c0 += kWave * CB) {
         typename V::type xc[CB], wc[EB][CB];
@@ -1167,10 +1169,14 @@ hipError_t launch_route_cache(hipStream_t s, int dtype, const RouteArgs& r, cons
     launch_timed(route_tile_kernel, dim3((a.B + 15) / 16), dim3(256), lds, s, ev, r, st, t, a);
     return hipGetLastError();
   }
-  if (dtype == MOE_DTYPE_FP32)
-    launch_timed(route_cache_kernel<float>, grid, block, lds, s, ev, r, st, t, a);
-  else
-    launch_timed(route_cache_kernel<uint16_t>, grid, block, lds, s, ev, r, st, t, a);
+  const bool one_row = a.E <= waves;
+  if (dtype == MOE_DTYPE_FP32) {
+    if (one_row) launch_timed(route_cache_kernel<float, 1>, grid, block, lds, s, ev, r, st, t, a);
+    else launch_timed(route_cache_kernel<float, 4>, grid, block, lds, s, ev, r, st, t, a);
+  } else {
+    if (one_row) launch_timed(route_cache_kernel<uint16_t, 1>, grid, block, lds, s, ev, r, st, t, a);
+    else launch_timed(route_cache_kernel<uint16_t, 4>, grid, block, lds, s, ev, r, st, t, a);
+  }
   return hipGetLastError();
 }
 

@@ -25,7 +25,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kGemmWaves = 4;     // row tiles per workgroup
+
 // k-blocks (of 32) staged per step: two for the gate/up pass, one for the down projection (measured: the down pass
 // has twice the workgroups over half the contraction length and runs 1.5x faster with the shorter stage)
 template <int NMAT>
@@ -39,11 +39,18 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
 // kTokTile: tokens per workgroup.  128 shares every weight fragment among more tokens; 64 needs half the
 // accumulators and LDS, so more workgroups run side by side and hide each other's load latency: faster while an
 // expert sees at most ~64 tokens (measured 169 against 212 us at 32 tokens per expert).
-template <int NMAT, int kTokTile>
+// kGemmWaves: row tiles (waves) per workgroup.  Eight waves share one staged token tile among 128 output rows,
+// which halves the staging work per weight byte: faster once experts see ~128 tokens (302 against 335 us at 1024
+// tokens per call, 488 against 576 us at 2048); four waves leave more workgroups per compute unit and are better
+// below that.
+template <int NMAT, int kTokTile, int kGemmWaves>
 __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
+  constexpr int kGemmThreads = 64 * kGemmWaves;
   constexpr int kColBlocks = kTokTile / 16;
   constexpr int kStageKb = kStageKbOf<NMAT>;
-  constexpr int kPieces = kTokTile * kStageKb * 4 / 256;     // 16-byte pieces of the token tile each thread stages per step
+  constexpr int kTotalPieces = kTokTile * kStageKb * 4;
+  constexpr int kPieces = (kTotalPieces + kGemmThreads - 1) / kGemmThreads;
+  constexpr bool kExact = kTotalPieces % kGemmThreads == 0;   // every thread stages kPieces pieces     // 16-byte pieces of the token tile each thread stages per step
   // [buffer][k-block in stage][column block][lane] x 16 bytes
   __shared__ u32x4 xs[2][kStageKb][kColBlocks][64];
   const int g = blockIdx.y;
@@ -83,11 +90,11 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   int dst[kPieces];
 #pragma unroll
   for (int i = 0; i < kPieces; ++i) {
-    const int idx = threadIdx.x + 256 * i;
+    const int idx = threadIdx.x + kGemmThreads * i;
     const int r = idx / (4 * kStageKb), sg = idx % (4 * kStageKb);   // token row of the tile, 16-byte segment of it
     const int kbl = sg >> 2, q = sg & 3;
-    dst[i] = (kbl * kColBlocks + (r >> 4)) * 64 + q * 16 + (r & 15);
-    if (r < n_tok) {
+    dst[i] = (kExact || idx < kTotalPieces) ? (kbl * kColBlocks + (r >> 4)) * 64 + q * 16 + (r & 15) : -1;
+    if ((kExact || idx < kTotalPieces) && r < n_tok) {
       if (NMAT == 2) {
         const int p = a.t.sorted_pair[gd.begin + tok0 + r];
         src[i] = reinterpret_cast<const uint16_t*>(a.x) + (size_t)(p / a.KS) * a.d + sg * 8;
@@ -101,7 +108,7 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   auto load_x = [&](u32x4 (&xr)[kPieces], int kb) {
 #pragma unroll
     for (int i = 0; i < kPieces; ++i) {
-      const int kbi = kb + ((threadIdx.x + 256 * i) % (4 * kStageKb)) / 4;   // k-block this piece belongs to
+      const int kbi = kb + ((threadIdx.x + kGemmThreads * i) % (4 * kStageKb)) / 4;   // k-block this piece belongs to
       xr[i] = (src[i] != nullptr && kbi < nkb) ? *reinterpret_cast<const u32x4*>(src[i] + (size_t)kb * 32)
                                                 : u32x4{0, 0, 0, 0};
     }
@@ -125,7 +132,8 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   load_x(xr, 0);
   load_w(wc, 0);
 #pragma unroll
-  for (int i = 0; i < kPieces; ++i) (&xs[0][0][0][0])[dst[i]] = xr[i];
+  for (int i = 0; i < kPieces; ++i)
+    if (kExact || dst[i] >= 0) (&xs[0][0][0][0])[dst[i]] = xr[i];
   __syncthreads();
 
   int buf = 0;
@@ -150,7 +158,8 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
     }
     if (more) {
 #pragma unroll
-      for (int i = 0; i < kPieces; ++i) (&xs[buf ^ 1][0][0][0])[dst[i]] = xr[i];
+      for (int i = 0; i < kPieces; ++i)
+        if (kExact || dst[i] >= 0) (&xs[buf ^ 1][0][0][0])[dst[i]] = xr[i];
 #pragma unroll
       for (int j = 0; j < kStageKb; ++j)
 #pragma unroll
@@ -192,15 +201,19 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, Ker
   const bool small_tile = a.fetch == 0 && (int64_t)a.max_count * a.KS <= (int64_t)64 * a.g_max;
   const int tok_tile = small_tile ? 64 : 128;
   const int tiles = (a.max_count + tok_tile - 1) / tok_tile;
-  dim3 block(64 * kGemmWaves);
-  dim3 g1((a.f / 16 + kGemmWaves - 1) / kGemmWaves, a.g_max, tiles);
-  dim3 g2((a.d / 16 + kGemmWaves - 1) / kGemmWaves, a.g_max, tiles);
+  const int waves = (small_tile || a.fetch != 0) ? 4 : 8;
+  dim3 block(64 * waves);
+  dim3 g1((a.f / 16 + waves - 1) / waves, a.g_max, tiles);
+  dim3 g2((a.d / 16 + waves - 1) / waves, a.g_max, tiles);
   if (small_tile) {
-    launch_timed(ffn_gemm_kernel<2, 64>, g1, block, 0, s, e1, a);
-    launch_timed(ffn_gemm_kernel<1, 64>, g2, block, 0, s, e2, a);
+    launch_timed(ffn_gemm_kernel<2, 64, 4>, g1, block, 0, s, e1, a);
+    launch_timed(ffn_gemm_kernel<1, 64, 4>, g2, block, 0, s, e2, a);
+  } else if (waves == 4) {
+    launch_timed(ffn_gemm_kernel<2, 128, 4>, g1, block, 0, s, e1, a);
+    launch_timed(ffn_gemm_kernel<1, 128, 4>, g2, block, 0, s, e2, a);
   } else {
-    launch_timed(ffn_gemm_kernel<2, 128>, g1, block, 0, s, e1, a);
-    launch_timed(ffn_gemm_kernel<1, 128>, g2, block, 0, s, e2, a);
+    launch_timed(ffn_gemm_kernel<2, 128, 8>, g1, block, 0, s, e1, a);
+    launch_timed(ffn_gemm_kernel<1, 128, 8>, g2, block, 0, s, e2, a);
   }
   return hipGetLastError();
 }

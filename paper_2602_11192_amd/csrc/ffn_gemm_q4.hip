@@ -101,7 +101,8 @@ __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
     const int idx = threadIdx.x + 256 * i;
     const int r = idx >> 4, sg = idx & 15;                     // token row of the tile, 16-byte segment of its 256 bytes
     const int kbl = sg >> 2, qq = sg & 3;
-    dst[i] = (kbl * kCb + (r >> 4)) * 64 + qq * 16 + (r & 15);
+    // the 16 lanes that write together hold one row's 16 (k-block, slice) pieces: the XOR spreads them over the banks
+    dst[i] = (kbl * kCb + (r >> 4)) * 64 + qq * 16 + ((r & 15) ^ (qq + 4 * kbl));
     if (r < n_tok) {
       if (NMAT == 2) {
         const int p = a.t.sorted_pair[gd.begin + tok0 + r];
@@ -187,7 +188,7 @@ __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
 #pragma unroll
         for (int cb = 0; cb < kCb; ++cb) {
           if (cb < n_cb) {      // uniform
-            const bf16x8 xa = __builtin_bit_cast(bf16x8, xs[buf][j][cb][lane]);
+            const bf16x8 xa = __builtin_bit_cast(bf16x8, xs[buf][j][cb][lane ^ (q + 4 * j)]);
             const f32x4 off = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa, minus136, zero, 0, 0, 0);
 #pragma unroll
             for (int m = 0; m < NA; ++m)

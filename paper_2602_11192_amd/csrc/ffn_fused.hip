@@ -28,6 +28,8 @@
 // gate/up fragments (with the matching token slices), then its W_d fragments -
 // with up to kDepth fragments in flight; the W_d loads are already under way
 // while the workgroup reduces h, so HBM never idles inside the workgroup.
+#include <algorithm>
+
 #include "device_utils.hpp"
 #include "moe_internal.hpp"
 
@@ -311,28 +313,44 @@ void launch_fused_waves(hipStream_t s, const FfnArgs& a, KernelEvents ev) {
 
 }  // namespace
 
-// Half chunks only for batch-1 calls (the number of groups is then known on the host: g_max), only when the
-// surplus over the last full round of whole chunks fits on half the compute units (beyond that some unit gets two
-// halves and nothing is gained), and only when a half chunk's share of the contraction keeps the ring hand-over
-// between the phases (both k-block counts per wave a multiple of the ring depth).
+namespace {
+
+// Rows of d_ff on the most loaded compute unit when `wholes` 32-row workgroups and then `halves` 16-row workgroups
+// are dealt round-robin to n units.
+int max_rows_per_unit(int wholes, int halves, int n) {
+  const int start = wholes % n, w_lo = wholes / n, h_lo = halves / n, h_extra = halves % n;
+  // units [start, n) hold w_lo wholes; the first h_extra units from `start` on (wrapping) hold one more half
+  int best = 32 * w_lo + 16 * (h_lo + (h_extra > 0 ? 1 : 0));
+  if (start > 0) best = std::max(best, 32 * (w_lo + 1) + 16 * (h_lo + (start + h_extra > n ? 1 : 0)));
+  return best;
+}
+
+}  // namespace
+
+// Half chunks only for batch-1 calls (the number of groups is then known on the host: g_max) and only when a half
+// chunk's share of the contraction keeps the ring hand-over between the phases (both k-block counts per wave a
+// multiple of the ring depth).  Among all cuts the one with the lightest most-loaded compute unit wins; ties go to
+// the cut with the fewest halves (fewer partial rows).
 FusedSplit fused_split(int d, int f, int batch, int g_max, int n_cus) {
   FusedSplit sp{f / 32, 0};
 #ifndef MOE_FUSED_HALVES
 #define MOE_FUSED_HALVES 1
 #endif
-  if (!MOE_FUSED_HALVES || batch != 1 || g_max < 1 || n_cus < 1) return sp;
-  const int chunks = (f / 32) * g_max;
-  const int waves = pick_waves(d, chunks);
+  if (!MOE_FUSED_HALVES || batch != 1 || g_max < 1 || n_cus < 1 || f < 32) return sp;
+  const int per = f / 32;
+  const int waves = pick_waves(d, per * g_max);
   if (waves == 0) return sp;
   const int na = (d / 32) / (waves / 2);
   if (na % kDepth != 0 || (na / 2) % kDepth != 0 || (d / 32) % waves != 0) return sp;
-  const int rounds = chunks / n_cus, surplus = chunks - rounds * n_cus;
-  if (rounds < 1 || surplus == 0 || 2 * surplus > n_cus) return sp;
-  const int n_full = rounds * n_cus / g_max;
-  if (n_full < 1 || n_full >= f / 32) return sp;
-  if (2 * g_max * (f / 32 - n_full) > n_cus) return sp;
-  sp.n_full = n_full;
-  sp.n_half = f / 32 - n_full;
+  int best = max_rows_per_unit(per * g_max, 0, n_cus);
+  for (int n_full = per - 1; n_full >= 0; --n_full) {
+    const int rows = max_rows_per_unit(g_max * n_full, 2 * g_max * (per - n_full), n_cus);
+    if (rows < best) {
+      best = rows;
+      sp.n_full = n_full;
+      sp.n_half = per - n_full;
+    }
+  }
   return sp;
 }
 

@@ -127,6 +127,21 @@ def test_one_layer_of_the_large_stacks(torch, P, name, fetch):
     cache.close()
 
 
+@pytest.mark.parametrize("fetch", ["copy_engine", "in_kernel"])
+def test_small_launch_runs_as_half_chunks(torch, P, fetch):
+    # 2 selected experts x 32 chunks are fewer workgroups than the GPU has compute units: every chunk of such a
+    # batch-1 call is cut into two 16-row halves
+    cfg = get_config("olmoe_like").with_(n_experts=8, top_k=2, capacity=4, n_seqs=3, n_steps=24, pref_lo=2, pref_hi=2)
+    wl = Workload(cfg)
+    mode = P.B.MOE_FETCH_IN_KERNEL if fetch == "in_kernel" else P.B.MOE_FETCH_COPY_ENGINE
+    cache = P.make_cache(wl, trace_capacity=4096, fetch_mode=mode)
+    ost = OracleStack(wl, keep=cfg.n_experts)
+    worst, n_y, traces = run_sequence_serial(wl, cache, ost, torch=torch, y_every=4)
+    compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
+    assert cache.moe_cache_stats()["misses"] > 0
+    cache.close()
+
+
 def test_deepseek_like_batched_shared_cache(torch, P):
     """Eight sequences decode together through one capacity-12 cache with two shared experts."""
     cfg = get_config("deepseek_like").with_(n_layers=1, n_seqs=8, n_steps=6)

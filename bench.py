@@ -414,6 +414,17 @@ def main():
         P.B.moe_probe_stream(src, dst, n, 1, 1)
         del src, dst
 
+    # what a plain streaming read sustains on this GPU in this run (boxes differ by several percent)
+    n_probe = 512 * 1000 * 1000
+    probe_src = torch.empty(n_probe, dtype=torch.uint8, device="cuda").random_(0, 255)
+    P.B.moe_probe_stream(probe_src, None, n_probe, 0, 3)
+    probe_ms = P.B.moe_probe_stream(probe_src, None, n_probe, 0, 20)
+    del probe_src
+    hbm_probe = {"read_GBps": n_probe / probe_ms / 1e6, "bytes": n_probe,
+                 "frac_of_peak": n_probe / probe_ms / 1e6 / HBM_PEAK_GBPS,
+                 "note": "plain streaming read of 512 MB by the library's probe kernel, same GPU, same run: the "
+                         "practical ceiling that roofline.achieved compares with"}
+
     cfg = get_config(a.workload)
     if a.layers:
         cfg = cfg.with_(n_layers=a.layers)
@@ -526,6 +537,7 @@ def main():
         "cache_hit_rate": st["hits"] / max(1, st["lookups"]),
         "misses_per_token": st["misses"] / max(1, n_tok),
         "roofline": roofline,
+        "hbm_probe": hbm_probe,
         "fetch_mode": a.fetch_mode,
         "pcie": ({"achieved": tm["fetch_bytes"] / (tm["fetch_ms"] * 1e-3) / 1e9 if tm["fetch_ms"] > 0 else None,
                   "peak": PCIE_PEAK_GBPS, "unit": "GB/s", "launches": tm["fetch_launches"],

@@ -18,18 +18,10 @@
 // The chunks of an expert are summed, in chunk order, by combine_chunks_kernel
 // together with the gate-weighted sum over experts of Eq. 2 (deterministic).
 //
-// Half chunks: a compute unit streams at a fixed rate however many workgroups it holds, so a launch lasts as
-// long as its most loaded unit.  When the number of chunks of a batch-1 call is not a multiple of the number of
-// compute units, the chunks beyond the last full round are cut into halves of 16 rows (one row tile; all waves
-// slice the contraction; phase B reads only its half of every W_d fragment), launched behind all whole chunks,
-// so that the surplus spreads over twice as many units (DeepSeekMoE-like layer: 352 chunks -> 256 + 192 halves).
-//
 // Each wave runs ONE software-pipelined stream over its fragments - first its
 // gate/up fragments (with the matching token slices), then its W_d fragments -
 // with up to kDepth fragments in flight; the W_d loads are already under way
 // while the workgroup reduces h, so HBM never idles inside the workgroup.
-#include <algorithm>
-
 #include "device_utils.hpp"
 #include "moe_internal.hpp"
 
@@ -73,26 +65,7 @@ template <int WAVES, int SLOT0>
 __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
   __shared__ float red[WAVES][2][256];            // partial gate / up tiles of the waves
   __shared__ __align__(16) uint16_t hs[16][32];   // h of the chunk, bf16, [token][row in chunk]
-  // whole chunks: grid (chunk, group); with half chunks: a 1-D grid, all whole chunks first, then the halves
-  int g, c, hf = 0;
-  bool is_half = false;
-  if (a.n_half == 0) {
-    g = blockIdx.y;
-    c = blockIdx.x;  // chunk of 32 intermediate rows
-  } else {
-    const int id = blockIdx.x, n_whole = a.g_max * a.n_full;
-    if (id < n_whole) {
-      g = id / a.n_full;
-      c = id - g * a.n_full;
-    } else {
-      const int r = id - n_whole, per = 2 * a.n_half;
-      g = r / per;
-      const int e = r - g * per;
-      c = a.n_full + (e >> 1);
-      hf = e & 1;     // which 16 rows of the chunk
-      is_half = true;
-    }
-  }
+  const int g = blockIdx.y;
   const int ng = *a.t.n_groups;        // both loads are issued before the first branch: one round trip
   const GroupDesc gd = a.t.grp[g];
   if (g >= ng || (a.pass != 2 && gd.miss != a.pass)) return;
@@ -101,17 +74,16 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
   const int wave = threadIdx.x >> 6;
   const int n = lane & 15;   // token column
   const int q = lane >> 4;   // 8-wide slice of a 32-deep k-block
+  const int c = blockIdx.x;  // chunk of 32 intermediate rows
   const int d = a.d;
   const int nkb_d = d >> 5, n_dt = d >> 4;
   constexpr int KS = WAVES / 2;
-  // whole chunk: 2 row tiles x WAVES/2 contraction slices; half chunk: its row tile x WAVES slices
-  const int tile = is_half ? hf : (wave & 1), ks = is_half ? wave : (wave >> 1);
-  const int n_slices = is_half ? WAVES : KS;
-  const int na = nkb_d / n_slices;   // gate/up k-blocks of this wave   (host guarantees divisibility)
-  const int nb = n_dt / WAVES;       // W_d row tiles of this wave
+  const int tile = wave & 1, ks = wave >> 1;
+  const int na = nkb_d / KS;      // gate/up k-blocks of this wave   (host guarantees divisibility)
+  const int nb = n_dt / WAVES;    // W_d row tiles of this wave
   // k-blocks are dealt round-robin to the contraction slices, so the waves of a row tile read
   // adjacent KiBs at any moment (measured 4 % faster than one contiguous run per wave)
-  const int kb0 = ks, kb_step = n_slices;
+  const int kb0 = ks, kb_step = KS;
 
   const size_t x_step = (size_t)kb_step * 32, w_step = (size_t)kb_step * 128;
   // a group whose expert is not resident yet reads it from the pinned host pool over PCIe and, on the way,
@@ -126,12 +98,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
   };
   // gate/up fragment (row tile 2c+tile, kb, m) and W_d fragment (chunk c, row tile dt)
   const u32x4* wa = wbase + ((size_t)(2 * c + tile) * nkb_d + kb0) * 2 * 64 + lane;
-  // a half chunk owns the lanes of its 16 rows in every W_d fragment; the other lanes read 16 bytes of the token
-  // instead (finite values that meet zeros of h), so that the loads need no branch
-  const bool b_on = !is_half || (q >> 1) == hf;
-  const u32x4* wb = b_on ? wbase + (size_t)2 * a.f * d / 8 + ((size_t)c * n_dt + wave) * 64 + lane
-                         : reinterpret_cast<const u32x4*>(a.x);
-  const size_t wb_step = b_on ? (size_t)WAVES * 64 : 0;
+  const u32x4* wb = wbase + (size_t)2 * a.f * d / 8 + ((size_t)c * n_dt + wave) * 64 + lane;
 
   const int begin = gd.begin, cnt = gd.count;
   const uint16_t* xrow = nullptr;
@@ -150,7 +117,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
       sg[slot] = ldw(wa + (size_t)item * w_step);
       su[slot] = ldw(wa + (size_t)item * w_step + 64);
     } else if (item < total) {
-      sg[slot] = ldw(wb + (size_t)(item - na) * wb_step);
+      sg[slot] = ldw(wb + (size_t)(item - na) * WAVES * 64);
     }
   };
 #pragma unroll
@@ -182,18 +149,10 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
     const int nn = r >> 4, mm = r & 15;                         // token, row inside the tile
     const int src = ((mm >> 2) * 16 + nn) * 4 + (mm & 3);       // where the MFMA left element (mm, nn)
     float vg = 0.f, vu = 0.f;
-    if (!is_half) {
 #pragma unroll
-      for (int k = 0; k < KS; ++k) {
-        vg += red[k * 2 + tl][0][src];
-        vu += red[k * 2 + tl][1][src];
-      }
-    } else if (tl == hf) {      // every wave holds a slice of the one row tile; the other 16 rows of h stay zero
-#pragma unroll
-      for (int k = 0; k < WAVES; ++k) {
-        vg += red[k][0][src];
-        vu += red[k][1][src];
-      }
+    for (int k = 0; k < KS; ++k) {
+      vg += red[k * 2 + tl][0][src];
+      vu += red[k * 2 + tl][1][src];
     }
     hs[nn][tl * 16 + mm] = nn < cnt ? f32_to_bf16(silu(vg) * vu) : (uint16_t)0;
   }
@@ -201,9 +160,8 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
 
   // ---- phase B: W_d[:, chunk] h; the first W_d fragments are already in their ring slots ----
   const bf16x8 hb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&hs[n][q * 8]));
-  const size_t n_rows = (size_t)(a.n_half == 0 ? (a.f >> 5) : a.n_full + 2 * a.n_half);   // partial rows per pair
-  const int prow = is_half ? a.n_full + 2 * (c - a.n_full) + hf : c;
-  float* obase = a.o + ((size_t)(begin + n) * n_rows + prow) * d + (lane >> 4) * 4;
+  const size_t n_chunks = (size_t)(a.f >> 5);
+  float* obase = a.o + ((size_t)(begin + n) * n_chunks + c) * d + (lane >> 4) * 4;
   // item (na + j) sits in ring slot (na + j) % kDepth: the slot sequence continues where phase A stopped
   for (int base = 0; base < nb; base += kDepth) {
 #pragma unroll
@@ -213,7 +171,7 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_kernel(FfnArgs a) {
         const int v = (SLOT0 + u) % kDepth;   // compile-time after unrolling
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, sg[v]), hb, acc, 0, 0, 0);
-        if (from_host && b_on) fill(wb + (size_t)j * wb_step, sg[v]);
+        if (from_host) fill(wb + (size_t)j * WAVES * 64, sg[v]);
         issue(v, na + j + kDepth);
         // lane holds rows (lane/16)*4 .. +3 of row tile (wave + WAVES j) for token n
         if (n < cnt)
@@ -301,7 +259,6 @@ int pick_waves(int d, int n_workgroups) {
 template <int WAVES>
 void launch_fused_waves(hipStream_t s, const FfnArgs& a, KernelEvents ev) {
   dim3 grid(a.f / 32, a.g_max), block(64 * WAVES);
-  if (a.n_half != 0) grid = dim3(a.g_max * (a.n_full + 2 * a.n_half));
   const int na = (a.d / 32) / (WAVES / 2);
   switch (na % kDepth) {
     case 0: launch_timed(ffn_fused_kernel<WAVES, 0>, grid, block, 0, s, ev, a); break;
@@ -313,47 +270,6 @@ void launch_fused_waves(hipStream_t s, const FfnArgs& a, KernelEvents ev) {
 
 }  // namespace
 
-namespace {
-
-// Rows of d_ff on the most loaded compute unit when `wholes` 32-row workgroups and then `halves` 16-row workgroups
-// are dealt round-robin to n units.
-int max_rows_per_unit(int wholes, int halves, int n) {
-  const int start = wholes % n, w_lo = wholes / n, h_lo = halves / n, h_extra = halves % n;
-  // units [start, n) hold w_lo wholes; the first h_extra units from `start` on (wrapping) hold one more half
-  int best = 32 * w_lo + 16 * (h_lo + (h_extra > 0 ? 1 : 0));
-  if (start > 0) best = std::max(best, 32 * (w_lo + 1) + 16 * (h_lo + (start + h_extra > n ? 1 : 0)));
-  return best;
-}
-
-}  // namespace
-
-// Half chunks only for batch-1 calls (the number of groups is then known on the host: g_max) and only when a half
-// chunk's share of the contraction keeps the ring hand-over between the phases (both k-block counts per wave a
-// multiple of the ring depth).  Among all cuts the one with the lightest most-loaded compute unit wins; ties go to
-// the cut with the fewest halves (fewer partial rows).
-FusedSplit fused_split(int d, int f, int batch, int g_max, int n_cus) {
-  FusedSplit sp{f / 32, 0};
-#ifndef MOE_FUSED_HALVES
-#define MOE_FUSED_HALVES 1
-#endif
-  if (!MOE_FUSED_HALVES || batch != 1 || g_max < 1 || n_cus < 1 || f < 32) return sp;
-  const int per = f / 32;
-  const int waves = pick_waves(d, per * g_max);
-  if (waves == 0) return sp;
-  const int na = (d / 32) / (waves / 2);
-  if (na % kDepth != 0 || (na / 2) % kDepth != 0 || (d / 32) % waves != 0) return sp;
-  int best = max_rows_per_unit(per * g_max, 0, n_cus);
-  for (int n_full = per - 1; n_full >= 0; --n_full) {
-    const int rows = max_rows_per_unit(g_max * n_full, 2 * g_max * (per - n_full), n_cus);
-    if (rows < best) {
-      best = rows;
-      sp.n_full = n_full;
-      sp.n_half = per - n_full;
-    }
-  }
-  return sp;
-}
-
 bool ffn_fused_supported(int d, int f, int max_count) {
   return max_count <= kFusedMaxTokens && f % 32 == 0 && pick_waves(d, 1) != 0;
 }
@@ -361,7 +277,7 @@ bool ffn_fused_supported(int d, int f, int max_count) {
 hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev) {
   if (a.g_max <= 0) return hipSuccess;
   // the grid is sized by an upper bound on the groups; batch 1 fills it exactly
-  switch (pick_waves(a.d, (a.f / 32) * a.g_max)) {    // by the number of chunks, whole or halved
+  switch (pick_waves(a.d, (a.f / 32) * a.g_max)) {
     case 4: launch_fused_waves<4>(s, a, ev); break;
     case 8: launch_fused_waves<8>(s, a, ev); break;
     case 16: launch_fused_waves<16>(s, a, ev); break;

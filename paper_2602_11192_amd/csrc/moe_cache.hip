@@ -69,7 +69,6 @@ struct moe_cache {
   moe_cache_config_t cfg{};
   moe_weights_t w{};
   int device = 0;
-  int n_cus = 0;                    // compute units of the device
   int C = 0, P = 0, KS = 0, G = 0;
   uint64_t expert_bytes = 0;
   size_t elem = 2;
@@ -481,7 +480,6 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
   c->t.grp = reinterpret_cast<GroupDesc*>(c->call_mem + o_gd);
   c->t.n_groups = reinterpret_cast<int32_t*>(c->call_mem + o_ng);
   c->arrive = reinterpret_cast<int32_t*>(c->call_mem + o_arr);
-  CREATE_CHK(hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev), MOE_ERR_HIP);
   CREATE_CHK(hipMalloc(&c->h, NP * cfg->d_ff * 4), MOE_ERR_HIP);
   size_t o_bytes = NP * cfg->d_model * 4;
   if (cfg->pool_layout == MOE_LAYOUT_TILED_INT4 ||
@@ -489,9 +487,6 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
     // the single-launch decode FFN keeps one partial sum per 32-row chunk of d_ff, for calls of up to 16 tokens
     const size_t pairs = (size_t)std::min(Bm, 16) * KS;
     o_bytes = std::max(o_bytes, pairs * (size_t)(cfg->d_ff / 32) * cfg->d_model * 4);
-    // a batch-1 call may cut part of the chunks into halves: more partial rows for its KS pairs
-    const FusedSplit sp = fused_split(cfg->d_model, cfg->d_ff, 1, KS, c->n_cus);
-    o_bytes = std::max(o_bytes, (size_t)KS * sp.rows() * cfg->d_model * 4);
   }
   CREATE_CHK(hipMalloc(reinterpret_cast<void**>(&c->o), o_bytes), MOE_ERR_HIP);
 
@@ -673,8 +668,6 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   // lookups, before the host knows the miss list.  With in-kernel fetch the same
   // launch also streams the missed experts from the host pool.
   const bool in_kernel = fused && cf.fetch_mode == MOE_FETCH_IN_KERNEL;
-  const FusedSplit split = fused_split(d, cf.d_ff, batch, fa.g_max, c->n_cus);   // single-launch bf16 kernel only
-  fa.n_full = split.n_full; fa.n_half = split.n_half;
   fa.pool = in_kernel ? c->pool_dev[layer] : nullptr;
   fa.fetch = in_kernel ? 1 : 0;
   fa.pass = in_kernel ? 2 : 0;
@@ -708,8 +701,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
     ps->used = true; ps->mixed = mb.n_miss > 0; ps->fused = fused;
     ps->fetched = in_kernel ? (uint64_t)mb.n_miss * c->expert_bytes : 0;
   }
-  HIPCHK(fused ? launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d,
-                                       q4w ? cf.d_ff / 32 : split.rows(), y_dev)
+  HIPCHK(fused ? launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev)
                : launch_combine(s, cf.dtype, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, y_dev));
 
   moe_cache_stats_t& st = c->stats[layer];

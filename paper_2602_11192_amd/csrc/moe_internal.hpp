@@ -91,17 +91,7 @@ struct FfnArgs {
   int32_t pass;            // 0: groups whose buffer was resident, 1: groups fetched by this call, 2: all
   const char* pool;        // in-kernel fetch: this layer's expert blocks in pinned host memory (device-visible)
   int32_t fetch;           // 1: groups with miss == 1 read their weights from `pool` and fill their buffer
-  int32_t n_full, n_half;  // single-launch bf16 kernel: whole 32-row chunks per group, and chunks cut into two halves
-                           // (n_half == 0: every chunk whole, n_full unused)
 };
-
-// How the single-launch bf16 kernel cuts a group's d_ff / 32 chunks for a call of `batch` tokens with (at most)
-// g_max groups on a device with n_cus compute units; rows() = partial output rows per (token, expert) pair.
-struct FusedSplit {
-  int n_full, n_half;
-  int rows() const { return n_full + 2 * n_half; }
-};
-FusedSplit fused_split(int d, int f, int batch, int g_max, int n_cus);
 
 // Router inputs of one call.
 struct RouteArgs {

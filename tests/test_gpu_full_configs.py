@@ -111,8 +111,6 @@ def test_olmoe_like_resident_path_batched(torch, P, olmoe, batch):
 @pytest.mark.parametrize("fetch", ["copy_engine", "in_kernel"])
 @pytest.mark.parametrize("name", ["mixtral_like", "phi35_like_concentrated", "phi35_like_diverse", "deepseek_like"])
 def test_one_layer_of_the_large_stacks(torch, P, name, fetch):
-    # (the Mixtral-like and DeepSeekMoE-like shapes take the launch with half chunks; with in-kernel fetch a half
-    # chunk also copies its half of every fragment of a missed expert into the device buffer)
     if fetch == "in_kernel" and name == "phi35_like_diverse":
         pytest.skip("same kernels as phi35_like_concentrated")
     cfg = get_config(name).with_(n_layers=1, n_seqs=2, n_steps=24)
@@ -128,9 +126,8 @@ def test_one_layer_of_the_large_stacks(torch, P, name, fetch):
 
 
 @pytest.mark.parametrize("fetch", ["copy_engine", "in_kernel"])
-def test_small_launch_runs_as_half_chunks(torch, P, fetch):
-    # 2 selected experts x 32 chunks are fewer workgroups than the GPU has compute units: every chunk of such a
-    # batch-1 call is cut into two 16-row halves
+def test_launch_smaller_than_the_gpu(torch, P, fetch):
+    # 2 selected experts x 32 chunks: fewer workgroups than the GPU has compute units
     cfg = get_config("olmoe_like").with_(n_experts=8, top_k=2, capacity=4, n_seqs=3, n_steps=24, pref_lo=2, pref_hi=2)
     wl = Workload(cfg)
     mode = P.B.MOE_FETCH_IN_KERNEL if fetch == "in_kernel" else P.B.MOE_FETCH_COPY_ENGINE

@@ -369,28 +369,35 @@ def cpu_baseline(wl, n_tokens):
     for l in range(cfg.n_layers):                      # parameter conversion is not part of the timed work
         for e in range(cfg.n_experts):
             ost.expert(l, e)
-    done, t_used = 0, 0.0
-    for s in range(cfg.n_seqs):
-        x32 = widen(wl.tokens(s))
-        for c in ost.caches:
-            c.reset()
-        for l in range(cfg.n_layers):
-            ost.caches[l].pin(wl.prefetch_list(l, s))
-        biases = [wl.bias(l, s)[None, :] for l in range(cfg.n_layers)]
-        t0 = time.perf_counter()
-        for t in range(cfg.n_steps):
+    def run(limit):
+        done, t_used = 0, 0.0
+        for s in range(cfg.n_seqs):
+            x32 = widen(wl.tokens(s))
+            for c in ost.caches:
+                c.reset()
             for l in range(cfg.n_layers):
-                ost.decode(l, x32[t:t + 1], biases[l])
-            done += 1
-            if done >= n_tokens:
+                ost.caches[l].pin(wl.prefetch_list(l, s))
+            biases = [wl.bias(l, s)[None, :] for l in range(cfg.n_layers)]
+            t0 = time.perf_counter()
+            for t in range(cfg.n_steps):
+                for l in range(cfg.n_layers):
+                    ost.decode(l, x32[t:t + 1], biases[l])
+                done += 1
+                if done >= limit:
+                    break
+            t_used += time.perf_counter() - t0
+            if done >= limit:
                 break
-        t_used += time.perf_counter() - t0
-        if done >= n_tokens:
-            break
+        return done, t_used
+
+    done, t_used = run(n_tokens)
     oracle.set_threads(1)
+    done1, t1 = run(max(1, n_tokens // 8))             # the same loops on one thread, shorter sample
     return {"value": done / t_used, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": "first %d decode tokens of the workload (sequence-serial, batch 1, all %d layer(s)), "
-                      "fp64 oracle with OpenMP over output rows" % (done, cfg.n_layers)}
+                      "fp64 oracle with OpenMP over output rows" % (done, cfg.n_layers),
+            "single_thread": {"value": done1 / t1, "unit": "tokens/s", "cores": 1,
+                              "sample": "first %d decode tokens, same loops on one thread" % done1}}
 
 
 def main():

@@ -4,14 +4,17 @@
 // offloading runtime of section 3.2).
 //
 // Order of one moe_layer_decode() call on the caller's stream:
-//   route kernel -> cache kernel -> [expert FFN over the groups whose expert was
-//   already resident] -> (host reads the miss list the cache kernel left in
-//   pinned memory; for each miss: hipMemcpyAsync pinned pool -> device buffer on
-//   the copy stream; the caller's stream waits for the copies) -> [expert FFN
-//   over the fetched groups] -> combine.
-// The FFN over resident experts is enqueued before the host looks at the miss
-// list, so the host round trip and the PCIe copies overlap that compute, as
-// Eq. 4's additive model (compute + N_miss * transfer) is the worst case.
+//   route_cache kernel (router, gating, cache lookups, grouping; leaves the miss list and the call's counters in a
+//   pinned mailbox) -> expert FFN -> combine.
+// Copy-engine fetch: the FFN over the groups whose expert was already resident is enqueued before the host looks
+// at the miss list; the host then reads the mailbox, issues one hipMemcpyAsync per miss (pinned pool -> device
+// buffer) on the copy stream, makes the caller's stream wait for them and enqueues the FFN over the fetched
+// groups.  The host round trip and the PCIe copies overlap the resident experts' compute: the additive model of
+// Eq. 4 (compute + N_miss * transfer) is the worst case.
+// In-kernel fetch: one FFN launch covers all groups; the workgroups of a missed expert read it from the mapped
+// pinned pool and fill its device buffer on the way.  The host still reads the mailbox (counters, status) while
+// that launch runs.
+// A call whose evictions need more spare buffers than exist is re-issued as two waves of tokens.
 #include <algorithm>
 #include <chrono>
 #include <cstdarg>

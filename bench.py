@@ -468,6 +468,15 @@ def main():
     n_tok_p, dt_p = timed(torch, run.pass_sequence_serial, a.steps)
     tm = cache.moe_cache_timing(clear=True)
     cache.moe_cache_set_profiling(False)
+
+    # the same schedule without the per-sequence prefetch: every sequence starts on an empty cache
+    run.pass_sequence_serial(pins=False)
+    cache.moe_cache_reset(-1, clear_stats=True)
+    n_cold, dt_cold = timed(torch, lambda: run.pass_sequence_serial(pins=False), max(1, a.steps // 4))
+    st_cold = cache.moe_cache_stats()
+    cold = {"tokens_per_s": n_cold / dt_cold, "cache_hit_rate": st_cold["hits"] / max(1, st_cold["lookups"]),
+            "misses_per_token": st_cold["misses"] / max(1, n_cold),
+            "note": "no prefetch set: the first tokens of a sequence miss until its experts are resident"}
     cache.close()
 
     # the same workload with the copy-engine fetch (hipMemcpyAsync on the copy stream), for comparison
@@ -558,6 +567,7 @@ def main():
                           "frac_of_hbm_peak_whole_call": layer_bytes * cfg.n_layers * res_tok_s / 1e9 / HBM_PEAK_GBPS,
                           "ffn_kernels_us": ffn_ms_r * 1e3,
                           "route_cache_us": rtm["route_ms"] / max(1, rtm["route_launches"]) * 1e3},
+        "cold_start": cold,
         "copy_engine_fetch": other,
         "miss_path": miss_path(torch, P, wl, pool, fetch_mode),
         "profiled_rerun_tokens_per_s": n_tok_p / dt_p,

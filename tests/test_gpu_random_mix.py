@@ -1,5 +1,6 @@
-"""Randomised parity: seeded mixes of shapes, policies, layouts, fetch modes, call sizes and spare-buffer counts
-through the C ABI against the oracle (routing and traces exact, outputs within the bf16 tolerance)."""
+"""Randomised parity: seeded mixes of shapes, policies, layouts, fetch modes, call sizes and spare-buffer counts,
+with resets, preloads and prompt calls in between, through the C ABI against the oracle (routing and traces exact,
+outputs within the bf16 tolerance)."""
 import random
 
 import numpy as np
@@ -56,6 +57,25 @@ def one_case(rng, torch, P):
                       gamma=1.0 if gamma is None else gamma, keep=E, int4=int4)
     trace = []
     for step, bsz in enumerate(batches):
+        r = rng.random()
+        if r < 0.15:                # drop the cache and preload a random set
+            ids = rng.sample(range(E), rng.randint(0, C))
+            cache.moe_cache_reset(0)
+            ost.caches[0].reset()
+            cache.moe_cache_prefill_pins(0, ids)
+            ost.caches[0].pin(ids)
+        elif r < 0.35 and tiled:    # a prompt through the layer: the cache is read, never changed
+            n_p = min(mb, rng.choice([1, 3, 17, mb]))
+            rows_p = [rng.randrange(mb) for _ in range(n_p)]
+            xs = np.stack([wl.tokens(s)[step] for s in rows_p])
+            bias = np.stack([wl.bias(0, s) for s in rows_p])
+            y = torch.empty((n_p, d_model), dtype=torch.bfloat16, device="cuda:0")
+            idx = torch.empty((n_p, K), dtype=torch.int32, device="cuda:0")
+            cache.moe_layer_prefill(0, P.to_device(xs), y, torch.from_numpy(bias).cuda(), idx, None)
+            res = ost.prefill(0, widen(xs), bias)
+            torch.cuda.synchronize()
+            assert idx.cpu().numpy().tolist() == res.idx.tolist(), what
+            assert rel_err(P.to_numpy(y), res.y).max() <= TOL["bf16"], what
         rows = list(range(bsz))
         xs = np.stack([wl.tokens(s)[step] for s in rows])
         bias = np.stack([wl.bias(0, s) for s in rows])

@@ -45,7 +45,7 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
                   : a.shared + (size_t)(id - a.P) * a.expert_bytes;
 }
 
-// kTokTile: tokens per workgroup.  128 shares every weight fragment among more tokens; 64 needs half the
+// kTokTile: tokens per workgroup (64, 128 or 256).  128 shares every weight fragment among more tokens; 64 needs half the
 // accumulators and LDS, so more workgroups run side by side and hide each other's load latency: faster while an
 // expert sees at most ~64 tokens (measured 169 against 212 us at 32 tokens per expert).
 // kGemmWaves: row tiles (waves) per workgroup.  Eight waves share one staged token tile among 128 output rows,
@@ -207,22 +207,42 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, Ker
   if (a.g_max <= 0) return hipSuccess;
   // the group sizes are not known on the host; the mean load decides the token tile
   // (experts streamed from the host are read once per token tile: the large tile keeps that to one read up to 128 tokens)
-  const bool small_tile = a.fetch == 0 && (int64_t)a.max_count * a.KS <= (int64_t)64 * a.g_max;
-  const int tok_tile = small_tile ? 64 : 128;
-  const int tiles = (a.max_count + tok_tile - 1) / tok_tile;
+  const int64_t load = (int64_t)a.max_count * a.KS;     // (token, expert) pairs of the call, all groups together
+#ifndef MOE_GEMM_SMALL_MAX
+#define MOE_GEMM_SMALL_MAX 24
+#endif
+  // (mean pairs per group; measured on the OLMoE-like layer: the 64-token tile on four waves is level with the
+  // 128-token tile on eight waves up to ~24 and loses beyond - 165 against 147 us at 32, 243 against 205 us at 64 -
+  // because the busier experts then need a second tile)
+  const bool small_tile = a.fetch == 0 && load <= (int64_t)MOE_GEMM_SMALL_MAX * a.g_max;
+  // 256-token tiles: an expert with 129-256 tokens then streams its weights once instead of twice.  The gate/up
+  // pass (both accumulator sets on the wave: 204 registers, one workgroup per compute unit) gains from a mean of ~52
+  // pairs per expert on (118 against 126 us at 56, 164 against 184 us at 128; 113 against 103 us at 48); the down pass, which runs two workgroups per unit
+  // with the 128-token tile, only from ~200 (180 against 188 us at 2048, but 126 against 109 us at 1024).
+#ifndef MOE_GEMM_BIG_UP
+#define MOE_GEMM_BIG_UP 52
+#endif
+  const bool big_up = a.fetch == 0 && load > (int64_t)MOE_GEMM_BIG_UP * a.g_max;
+#ifndef MOE_GEMM_BIG_DOWN
+#define MOE_GEMM_BIG_DOWN 192
+#endif
+  const bool big_down = a.fetch == 0 && load > (int64_t)MOE_GEMM_BIG_DOWN * a.g_max;
   const int waves = (small_tile || a.fetch != 0) ? 4 : 8;
-  dim3 block(64 * waves);
-  dim3 g1((a.f / 16 + waves - 1) / waves, a.g_max, tiles);
-  dim3 g2((a.d / 16 + waves - 1) / waves, a.g_max, tiles);
+  const dim3 block(64 * waves);
+  auto grid = [&](int rows, int tok_tile) {
+    return dim3((rows / 16 + waves - 1) / waves, a.g_max, (a.max_count + tok_tile - 1) / tok_tile);
+  };
   if (small_tile) {
-    launch_timed(ffn_gemm_kernel<2, 64, 4>, g1, block, 0, s, e1, a);
-    launch_timed(ffn_gemm_kernel<1, 64, 4>, g2, block, 0, s, e2, a);
+    launch_timed(ffn_gemm_kernel<2, 64, 4>, grid(a.f, 64), block, 0, s, e1, a);
+    launch_timed(ffn_gemm_kernel<1, 64, 4>, grid(a.d, 64), block, 0, s, e2, a);
   } else if (waves == 4) {
-    launch_timed(ffn_gemm_kernel<2, 128, 4>, g1, block, 0, s, e1, a);
-    launch_timed(ffn_gemm_kernel<1, 128, 4>, g2, block, 0, s, e2, a);
+    launch_timed(ffn_gemm_kernel<2, 128, 4>, grid(a.f, 128), block, 0, s, e1, a);
+    launch_timed(ffn_gemm_kernel<1, 128, 4>, grid(a.d, 128), block, 0, s, e2, a);
   } else {
-    launch_timed(ffn_gemm_kernel<2, 128, 8>, g1, block, 0, s, e1, a);
-    launch_timed(ffn_gemm_kernel<1, 128, 8>, g2, block, 0, s, e2, a);
+    if (big_up) launch_timed(ffn_gemm_kernel<2, 256, 8>, grid(a.f, 256), block, 0, s, e1, a);
+    else launch_timed(ffn_gemm_kernel<2, 128, 8>, grid(a.f, 128), block, 0, s, e1, a);
+    if (big_down) launch_timed(ffn_gemm_kernel<1, 256, 8>, grid(a.d, 256), block, 0, s, e2, a);
+    else launch_timed(ffn_gemm_kernel<1, 128, 8>, grid(a.d, 128), block, 0, s, e2, a);
   }
   return hipGetLastError();
 }

@@ -58,7 +58,7 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
 }
 
 // kTok: tokens per workgroup (64 or 128).  An expert streamed from the host is read once per token tile, so prompt
-// streaming takes the large tile; the small one needs half the accumulators.
+// streaming takes the large tile; the small one needs half the accumulators and serves every resident call.
 template <int NMAT, int kTok>
 __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
   constexpr int kCb = kTok / 16;      // column blocks of 16 tokens
@@ -233,7 +233,11 @@ __global__ void __launch_bounds__(64 * kWaves) ffn_gemm_q4_kernel(FfnArgs a) {
 
 hipError_t launch_ffn_gemm_q4(hipStream_t s, const FfnArgs& a, KernelEvents e1, KernelEvents e2) {
   if (a.g_max <= 0) return hipSuccess;
-  const bool large_tile = a.fetch != 0 || (int64_t)a.max_count * a.KS > (int64_t)64 * a.g_max;
+  // 128-token tiles only when experts stream in from the host (each tile reads the expert over the link once).
+  // On resident experts the 64-token tile is faster at every call size measured (OLMoE-like layer: 71 against
+  // 127 us at 64 tokens per call, 280 against 413 us at 1024, 505 against 717 us at 2048): half the accumulators,
+  // twice the workgroups per compute unit.
+  const bool large_tile = a.fetch != 0;
   const int tok = large_tile ? 128 : 64;
   const int tiles = (a.max_count + tok - 1) / tok;
   dim3 block(64 * kWaves);

@@ -1053,25 +1053,25 @@ __device__ void cache_phase_fast_wide(unsigned char* smem, const LdsLayout& L, c
   }
 }
 
-// Phases 1 and 2 for calls of many bf16 tokens: a workgroup of 4 waves routes a tile of 16 tokens.  The
+// Phases 1 and 2 for calls of many bf16 tokens: a workgroup (eight waves) routes a tile of 16 tokens.  The
 // router logits of the tile are one small matrix product (experts x tokens) on the matrix cores: the rows of W_r
 // are the A operand and the tokens the B operand of v_mfma_f32_16x16x32_bf16, both read straight from global
-// memory in operand order, so W_r is read once per 16 tokens instead of once per token.  Each wave then gates
-// four of the tokens.  The last workgroup to arrive runs phase 3 with all its waves.
-__global__ void __launch_bounds__(256) route_tile_kernel(RouteArgs r, LayerState st, CallTables t, CacheCallArgs a) {
+// memory in operand order, so W_r is read once per 16 tokens instead of once per token.  The waves then gate
+// the 16 tokens between them.  The last workgroup to arrive runs phase 3 with all its waves.
+__global__ void __launch_bounds__(1024) route_tile_kernel(RouteArgs r, LayerState st, CallTables t, CacheCallArgs a) {
   typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
   extern __shared__ __align__(8) unsigned char smem[];
   __shared__ float zs_tile[16][kTileMaxE];
   __shared__ int s_last;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
   const int n = lane & 15, q = lane >> 4;
   const int E = a.E, K = a.K, KS = a.KS, d = r.d;
   const int t0 = blockIdx.x * 16;
   const int nkb = d >> 5;
   const uint16_t* xrow = (t0 + n < a.B) ? static_cast<const uint16_t*>(r.x) + (size_t)(t0 + n) * d + q * 8 : nullptr;
-  for (int e0 = wave * 16; e0 < E; e0 += 64) {          // expert tiles of this wave
+  for (int e0 = wave * 16; e0 < E; e0 += 16 * n_waves) {          // expert tiles of this wave
     const int er = e0 + n < E ? e0 + n : E - 1;         // clamped: in bounds, dropped below
     const uint16_t* wrow = static_cast<const uint16_t*>(r.router_w) + (size_t)er * d + q * 8;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -1098,7 +1098,7 @@ __global__ void __launch_bounds__(256) route_tile_kernel(RouteArgs r, LayerState
     }
   }
   __syncthreads();
-  for (int tt = wave; tt < 16 && t0 + tt < a.B; tt += 4) {
+  for (int tt = wave; tt < 16 && t0 + tt < a.B; tt += n_waves) {
     if (E <= 64) gate_token<1>(zs_tile[tt], t0 + tt, E, K, KS, r.norm_topk, t.idx, t.wpair, r.user_idx, r.user_w, nullptr);
     else gate_token<kTileMaxE / 64>(zs_tile[tt], t0 + tt, E, K, KS, r.norm_topk, t.idx, t.wpair, r.user_idx, r.user_w,
                                     nullptr);
@@ -1166,7 +1166,10 @@ hipError_t launch_route_cache(hipStream_t s, int dtype, const RouteArgs& r, cons
   // from about a hundred tokens on, routing 16 tokens per workgroup on the matrix cores and running the cache
   // phase on four waves wins (measured: 36 against 48 us at 256 tokens, 61 against 182 us at 1024; 30 against 23 at 64)
   if (dtype == MOE_DTYPE_BF16 && a.B >= 128 && a.E <= kTileMaxE && r.d % 32 == 0) {
-    launch_timed(route_tile_kernel, dim3((a.B + 15) / 16), dim3(256), lds, s, ev, r, st, t, a);
+#ifndef MOE_ROUTE_TILE_WAVES
+#define MOE_ROUTE_TILE_WAVES 8      // measured: 49 us at 1024 tokens against 61 with four waves and 54 with sixteen
+#endif
+    launch_timed(route_tile_kernel, dim3((a.B + 15) / 16), dim3(64 * MOE_ROUTE_TILE_WAVES), lds, s, ev, r, st, t, a);
     return hipGetLastError();
   }
   const bool one_row = a.E <= waves;

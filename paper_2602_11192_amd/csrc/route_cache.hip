@@ -1164,8 +1164,9 @@ hipError_t launch_route_cache(hipStream_t s, int dtype, const RouteArgs& r, cons
   dim3 grid(a.B), block(64 * waves);
   const size_t lds = route_cache_lds_bytes(a.E, a.C, a.P, a.n_shared, a.B, a.K, a.KS);
   // from about a hundred tokens on, routing 16 tokens per workgroup on the matrix cores and running the cache
-  // phase on four waves wins (measured: 36 against 48 us at 256 tokens, 61 against 182 us at 1024; 30 against 23 at 64)
-  if (dtype == MOE_DTYPE_BF16 && a.B >= 128 && a.E <= kTileMaxE && r.d % 32 == 0) {
+  // phase on all waves of the last workgroup wins (measured: 31 against 48 us at 256 tokens, 49 against 182 us at 1024;
+  // 28.6 against 26.6 at 96, 29.3 against 31.6 at 127)
+  if (dtype == MOE_DTYPE_BF16 && a.B >= 112 && a.E <= kTileMaxE && r.d % 32 == 0) {
 #ifndef MOE_ROUTE_TILE_WAVES
 #define MOE_ROUTE_TILE_WAVES 8      // measured: 49 us at 1024 tokens against 61 with four waves and 54 with sixteen
 #endif

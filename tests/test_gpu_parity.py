@@ -344,10 +344,11 @@ def test_odd_widths_take_the_generic_kernels(torch, P, d_model, d_ff):
     (100, 6, 100, 0, 200, "lru"),    # 64 < E <= 256, table larger than a wave (LDS table)
     (64, 8, 64, 2, 144, "lru"),      # 64 slots, 64 buffers, shared experts
     (16, 4, 8, 0, 140, "gamma"),     # discounted-count policy
+    (32, 4, 32, 0, 113, "lru"),      # just above the size from which the tile kernel is used, ragged last tile
 ])
 def test_large_calls_route_in_tiles_of_16_tokens(torch, P, E, K, C, n_shared, batch, policy):
-    # calls of 128 tokens and more: router logits of 16 tokens per workgroup on the matrix cores, cache phase on
-    # four waves; routing, traces and outputs must not depend on which kernel ran
+    # calls of 112 tokens and more: router logits of 16 tokens per workgroup on the matrix cores, cache phase on
+    # all waves of the last workgroup; routing, traces and outputs must not depend on which kernel ran
     from paper_2602_11192_amd import binding as B
     cfg = small_cfg(n_experts=E, top_k=K, capacity=C, n_shared=n_shared, n_seqs=batch, n_steps=3, n_layers=1,
                     d_model=256, d_ff=64, beta=1.0, pref_lo=min(4, K), pref_hi=min(4, K))

@@ -68,18 +68,41 @@ __global__ void __launch_bounds__(64 * kRowsPerBlock) down_rowmajor(FfnArgs a) {
   }
 }
 
-// y[b][i] = sum_j wpair[b][j] * o[pos_of[b][j]][i], j over the K selected then the shared experts
+// y[b][i] = sum_j wpair[b][j] * o[pos_of[b][j]][i], j over the K selected then the shared experts.
+// A thread owns four consecutive columns (16-byte loads); the rows of a batch of pairs are all requested before
+// the first is used; the pairs are added in index order, so the result does not depend on the batch size.
+typedef float f32x4_c __attribute__((ext_vector_type(4)));
+constexpr int kCombinePairs = 8;
+
 template <typename T>
 __global__ void __launch_bounds__(256)
 combine_kernel(const float* __restrict__ o, const float* __restrict__ wpair, const int32_t* __restrict__ pos_of,
                int KS, int d, T* __restrict__ y) {
   const int b = blockIdx.x;
-  const int i = blockIdx.y * blockDim.x + threadIdx.x;
+  const int i = (blockIdx.y * blockDim.x + threadIdx.x) * 4;      // host guarantees d % 4 == 0
   if (i >= d) return;
-  float acc = 0.f;
-  for (int j = 0; j < KS; ++j)
-    acc = fmaf(wpair[(size_t)b * KS + j], o[(size_t)pos_of[(size_t)b * KS + j] * d + i], acc);
-  Elem<T>::store(y + (size_t)b * d + i, acc);
+  const float* wrow = wpair + (size_t)b * KS;
+  const int32_t* prow = pos_of + (size_t)b * KS;
+  f32x4_c acc = {0.f, 0.f, 0.f, 0.f};
+  for (int j0 = 0; j0 < KS; j0 += kCombinePairs) {
+    f32x4_c v[kCombinePairs];
+    float w[kCombinePairs];
+#pragma unroll
+    for (int u = 0; u < kCombinePairs; ++u) {
+      const int j = j0 + u < KS ? j0 + u : KS - 1;          // clamped: in bounds, weight zeroed below
+      w[u] = j0 + u < KS ? wrow[j] : 0.f;
+      v[u] = *reinterpret_cast<const f32x4_c*>(o + (size_t)prow[j] * d + i);
+    }
+#pragma unroll
+    for (int u = 0; u < kCombinePairs; ++u) {
+      if (j0 + u < KS) {      // uniform
+#pragma unroll
+        for (int c = 0; c < 4; ++c) acc[c] = fmaf(w[u], v[u][c], acc[c]);
+      }
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 4; ++c) Elem<T>::store(y + (size_t)b * d + i + c, acc[c]);
 }
 
 }  // namespace
@@ -101,7 +124,7 @@ hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, Kerne
 
 hipError_t launch_combine(hipStream_t s, int dtype, const float* o, const float* wpair, const int32_t* pos_of,
                           int B, int KS, int d, void* y) {
-  dim3 grid(B, (d + 255) / 256), block(256);
+  dim3 grid(B, (d / 4 + 255) / 256), block(256);
   if (dtype == MOE_DTYPE_FP32)
     hipLaunchKernelGGL(combine_kernel<float>, grid, block, 0, s, o, wpair, pos_of, KS, d, (float*)y);
   else

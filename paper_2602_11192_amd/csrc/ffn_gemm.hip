@@ -37,7 +37,7 @@ constexpr int kStageKbOf = NMAT == 2 ? 2 : 1;
 // applies the same value (measured: 4 % faster at 1024-2048 tokens per call).
 template <int kStageKb>
 __device__ __forceinline__ int swz(int q, int kbl) {
-  return kStageKb == 2 ? (q + 4 * kbl) * 2 : q * 4;
+  return kStageKb == 4 ? q + 4 * kbl : kStageKb == 2 ? (q + 4 * kbl) * 2 : q * 4;
 }
 
 __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
@@ -52,11 +52,14 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
 // which halves the staging work per weight byte: faster once experts see ~128 tokens (302 against 335 us at 1024
 // tokens per call, 488 against 576 us at 2048); four waves leave more workgroups per compute unit and are better
 // below that.
-template <int NMAT, int kTokTile, int kGemmWaves>
+// kSkb: k-blocks staged per step.  The default (two for gate/up, one for the down pass) suits launches with many
+// workgroups per compute unit; a down pass with few workgroups and a long contraction (Mixtral-like: 512
+// workgroups, 448 k-blocks) is bound by the latency of its one-KiB-per-wave steps and takes four k-blocks per step.
+template <int NMAT, int kTokTile, int kGemmWaves, int kSkb = kStageKbOf<NMAT>>
 __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   constexpr int kGemmThreads = 64 * kGemmWaves;
   constexpr int kColBlocks = kTokTile / 16;
-  constexpr int kStageKb = kStageKbOf<NMAT>;
+  constexpr int kStageKb = kSkb;
   constexpr int kTotalPieces = kTokTile * kStageKb * 4;
   constexpr int kPieces = (kTotalPieces + kGemmThreads - 1) / kGemmThreads;
   constexpr bool kExact = kTotalPieces % kGemmThreads == 0;   // every thread stages kPieces pieces     // 16-byte pieces of the token tile each thread stages per step
@@ -228,22 +231,29 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, Ker
 #endif
   const bool big_down = a.fetch == 0 && load > (int64_t)MOE_GEMM_BIG_DOWN * a.g_max;
   const int waves = (small_tile || a.fetch != 0) ? 4 : 8;
-  const dim3 block(64 * waves);
-  auto grid = [&](int rows, int tok_tile) {
-    return dim3((rows / 16 + waves - 1) / waves, a.g_max, (a.max_count + tok_tile - 1) / tok_tile);
+  auto grid = [&](int rows, int tok_tile, int wv) {
+    return dim3((rows / 16 + wv - 1) / wv, a.g_max, (a.max_count + tok_tile - 1) / tok_tile);
   };
-  if (small_tile) {
-    launch_timed(ffn_gemm_kernel<2, 64, 4>, grid(a.f, 64), block, 0, s, e1, a);
-    launch_timed(ffn_gemm_kernel<1, 64, 4>, grid(a.d, 64), block, 0, s, e2, a);
-  } else if (waves == 4) {
-    launch_timed(ffn_gemm_kernel<2, 128, 4>, grid(a.f, 128), block, 0, s, e1, a);
-    launch_timed(ffn_gemm_kernel<1, 128, 4>, grid(a.d, 128), block, 0, s, e2, a);
-  } else {
-    if (big_up) launch_timed(ffn_gemm_kernel<2, 256, 8>, grid(a.f, 256), block, 0, s, e1, a);
-    else launch_timed(ffn_gemm_kernel<2, 128, 8>, grid(a.f, 128), block, 0, s, e1, a);
-    if (big_down) launch_timed(ffn_gemm_kernel<1, 256, 8>, grid(a.d, 256), block, 0, s, e2, a);
-    else launch_timed(ffn_gemm_kernel<1, 128, 8>, grid(a.d, 128), block, 0, s, e2, a);
-  }
+  const dim3 b4(64 * 4), b8(64 * 8);
+  // ---- gate/up ----
+  if (small_tile) launch_timed(ffn_gemm_kernel<2, 64, 4>, grid(a.f, 64, 4), b4, 0, s, e1, a);
+  else if (waves == 4) launch_timed(ffn_gemm_kernel<2, 128, 4>, grid(a.f, 128, 4), b4, 0, s, e1, a);
+  else if (big_up) launch_timed(ffn_gemm_kernel<2, 256, 8>, grid(a.f, 256, 8), b8, 0, s, e1, a);
+  else launch_timed(ffn_gemm_kernel<2, 128, 8>, grid(a.f, 128, 8), b8, 0, s, e1, a);
+  // ---- down ----
+#ifndef MOE_GEMM_DEEP_DOWN
+#define MOE_GEMM_DEEP_DOWN 1
+#endif
+  // A long contraction with few output rows (Mixtral-like: d_ff = 14336, 8 experts) leaves the down pass with one
+  // or two workgroups per compute unit, each waiting for one KiB per wave and step: four k-blocks per step and the
+  // 64-row workgroups (measured on that layer: 205 against 314 us at 8 tokens per call).
+  const bool deep_down = MOE_GEMM_DEEP_DOWN && small_tile && a.f >= 4096 &&
+                         (int64_t)((a.d / 16 + 3) / 4) * a.g_max < 4 * 256;
+  if (deep_down) launch_timed(ffn_gemm_kernel<1, 64, 4, 4>, grid(a.d, 64, 4), b4, 0, s, e2, a);
+  else if (small_tile) launch_timed(ffn_gemm_kernel<1, 64, 4>, grid(a.d, 64, 4), b4, 0, s, e2, a);
+  else if (waves == 4) launch_timed(ffn_gemm_kernel<1, 128, 4>, grid(a.d, 128, 4), b4, 0, s, e2, a);
+  else if (big_down) launch_timed(ffn_gemm_kernel<1, 256, 8>, grid(a.d, 256, 8), b8, 0, s, e2, a);
+  else launch_timed(ffn_gemm_kernel<1, 128, 8>, grid(a.d, 128, 8), b8, 0, s, e2, a);
   return hipGetLastError();
 }
 

@@ -139,6 +139,32 @@ def test_launch_smaller_than_the_gpu(torch, P, fetch):
     cache.close()
 
 
+def test_mixtral_like_batched_resident_decode(torch, P):
+    """Eight tokens per call on the Mixtral-like layer: the grouped GEMM with the long contraction of its down pass
+    (d_ff = 14336: four k-blocks per step) and few workgroups per compute unit."""
+    cfg = get_config("mixtral_like").with_(n_layers=1, n_seqs=8, n_steps=2, capacity=8)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, max_batch=8, trace_capacity=4096)
+    ost = OracleStack(wl, capacity=8, keep=8)
+    ids = list(range(cfg.n_experts))
+    cache.moe_cache_prefill_pins(0, ids)
+    ost.caches[0].pin(ids)
+    trace = []
+    for step in range(cfg.n_steps):
+        xs = np.stack([wl.tokens(s)[step] for s in range(8)])
+        bias = np.stack([wl.bias(0, s) for s in range(8)])
+        y = torch.empty((8, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+        idx = torch.empty((8, cfg.top_k), dtype=torch.int32, device="cuda:0")
+        cache.moe_layer_decode(0, P.to_device(xs), y, torch.from_numpy(bias).cuda(), idx, None)
+        res = ost.decode(0, widen(xs), bias)
+        torch.cuda.synchronize()
+        assert idx.cpu().numpy().tolist() == res.idx.tolist()
+        assert rel_err(P.to_numpy(y), res.y).max() <= TOL["bf16"]
+        trace += res.trace
+    compare_traces_and_stats(cache, ost, [trace], cfg.expert_bytes)
+    cache.close()
+
+
 def test_deepseek_like_batched_shared_cache(torch, P):
     """Eight sequences decode together through one capacity-12 cache with two shared experts."""
     cfg = get_config("deepseek_like").with_(n_layers=1, n_seqs=8, n_steps=6)

@@ -250,7 +250,7 @@ int pick_waves(int d, int n_workgroups) {
 #ifdef MOE_FUSED_FORCE_WAVES
   if (waves_ok(d, MOE_FUSED_FORCE_WAVES)) return MOE_FUSED_FORCE_WAVES;
 #endif
-  const int pref = n_workgroups <= 384 ? 8 : 4;
+  const int pref = n_workgroups <= 256 ? 8 : 4;     // eight waves only while every workgroup has a compute unit to itself
   for (int w : {pref, 8, 4, 16})
     if (waves_ok(d, w)) return w;
   return 0;

@@ -56,7 +56,7 @@ enum { MOE_LAYOUT_ROWMAJOR = 0, MOE_LAYOUT_TILED = 1, MOE_LAYOUT_TILED_INT4 = 2 
 /*
  * MOE_FETCH_COPY_ENGINE  hipMemcpyAsync from the pinned pool on the library's copy stream, ordered by events
  *                        before the FFN pass over the fetched experts; the FFN over resident experts overlaps it.
- * MOE_FETCH_IN_KERNEL    small decode calls (up to 6 tokens bf16, 16 tokens INT4) on a tiled layout: the expert kernel itself reads a
+ * MOE_FETCH_IN_KERNEL    small decode calls (up to 6 tokens bf16 - 8 when d_ff >= 4096 -, 16 tokens INT4) on a tiled layout: the expert kernel itself reads a
  *                        missed expert from the pinned pool over PCIe while it computes, and fills the device
  *                        buffer on the way; no copy engine and no host round trip on the miss path.  Calls the
  *                        single-launch kernel does not cover, and prefill_pins, use the copy engine.

@@ -271,7 +271,7 @@ void launch_fused_waves(hipStream_t s, const FfnArgs& a, KernelEvents ev) {
 }  // namespace
 
 bool ffn_fused_supported(int d, int f, int max_count) {
-  return max_count <= kFusedMaxTokens && f % 32 == 0 && pick_waves(d, 1) != 0;
+  return max_count <= fused_max_tokens(f) && f % 32 == 0 && pick_waves(d, 1) != 0;
 }
 
 hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev) {

@@ -664,7 +664,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   // on: 119 against 139 us at 17 tokens, 138 against 190 us at 128 on the OLMoE-like layer, and faster than the
   // single-launch kernel from about 6 tokens: 90 against 96 us at 8, 123 against 136 us at 16).  The split-K
   // pair remains for small calls on shapes the single-launch kernel does not cover.
-  const bool gemm = tiled && !fused && batch > kFusedMaxTokens;
+  const bool gemm = tiled && !fused && batch > fused_max_tokens(cf.d_ff);
   const KernelEvents ke1 = ps ? ps->gate_up : KernelEvents{}, ke2 = ps ? ps->down : KernelEvents{};
 
   // Experts that were already resident: their FFN starts right behind the cache

@@ -125,6 +125,10 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents gate_up
 // whole call is faster with the grouped GEMM from about 6 tokens on: 109 against 110 us at 6, 119 against 133 us
 // at 8 on the OLMoE-like layer).
 constexpr int kFusedMaxTokens = 6;
+// Shapes with a long contraction in the down pass (d_ff >= 4096) keep the single-launch kernel up to 8 tokens: the
+// grouped GEMM's down pass is the weaker one there (Phi-like layer: 286 against 337 us at 7 tokens, 312 against 332 us
+// at 8; Mixtral-like: 488 against 510 us at 7, level at 8; from 12 tokens on the GEMM wins on both).
+inline int fused_max_tokens(int d_ff) { return d_ff >= 4096 ? 8 : kFusedMaxTokens; }
 bool ffn_fused_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 bool ffn_fused_q4_supported(int d, int f, int max_count);

@@ -139,22 +139,23 @@ def test_launch_smaller_than_the_gpu(torch, P, fetch):
     cache.close()
 
 
-def test_mixtral_like_batched_resident_decode(torch, P):
-    """Eight tokens per call on the Mixtral-like layer: the grouped GEMM with the long contraction of its down pass
-    (d_ff = 14336: four k-blocks per step) and few workgroups per compute unit."""
-    cfg = get_config("mixtral_like").with_(n_layers=1, n_seqs=8, n_steps=2, capacity=8)
+@pytest.mark.parametrize("batch", [8, 12])
+def test_mixtral_like_batched_resident_decode(torch, P, batch):
+    """Several tokens per call on the Mixtral-like layer (d_ff = 14336): 8 tokens still take the single-launch
+    kernel, 12 the grouped GEMM, whose down pass runs four k-blocks per step on this long contraction."""
+    cfg = get_config("mixtral_like").with_(n_layers=1, n_seqs=batch, n_steps=2, capacity=8)
     wl = Workload(cfg)
-    cache = P.make_cache(wl, max_batch=8, trace_capacity=4096)
+    cache = P.make_cache(wl, max_batch=batch, trace_capacity=4096)
     ost = OracleStack(wl, capacity=8, keep=8)
     ids = list(range(cfg.n_experts))
     cache.moe_cache_prefill_pins(0, ids)
     ost.caches[0].pin(ids)
     trace = []
     for step in range(cfg.n_steps):
-        xs = np.stack([wl.tokens(s)[step] for s in range(8)])
-        bias = np.stack([wl.bias(0, s) for s in range(8)])
-        y = torch.empty((8, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
-        idx = torch.empty((8, cfg.top_k), dtype=torch.int32, device="cuda:0")
+        xs = np.stack([wl.tokens(s)[step] for s in range(batch)])
+        bias = np.stack([wl.bias(0, s) for s in range(batch)])
+        y = torch.empty((batch, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+        idx = torch.empty((batch, cfg.top_k), dtype=torch.int32, device="cuda:0")
         cache.moe_layer_decode(0, P.to_device(xs), y, torch.from_numpy(bias).cuda(), idx, None)
         res = ost.decode(0, widen(xs), bias)
         torch.cuda.synchronize()

@@ -166,6 +166,30 @@ def test_mixtral_like_batched_resident_decode(torch, P, batch):
     cache.close()
 
 
+def test_phi_like_batched_resident_decode(torch, P):
+    """All 32 sequences of the Phi-like workload decode together on a resident layer: the grouped GEMM at
+    d = 4096, d_ff = 6400 (100 row blocks of 64, ragged against the 128-row workgroups of larger calls)."""
+    cfg = get_config("phi35_like_concentrated").with_(n_layers=1, n_steps=1, capacity=16)
+    wl = Workload(cfg)
+    B_ = cfg.n_seqs
+    cache = P.make_cache(wl, max_batch=B_, trace_capacity=4096)
+    ost = OracleStack(wl, capacity=16, keep=16)
+    ids = list(range(cfg.n_experts))
+    cache.moe_cache_prefill_pins(0, ids)
+    ost.caches[0].pin(ids)
+    xs = np.stack([wl.tokens(s)[0] for s in range(B_)])
+    bias = np.stack([wl.bias(0, s) for s in range(B_)])
+    y = torch.empty((B_, cfg.d_model), dtype=torch.bfloat16, device="cuda:0")
+    idx = torch.empty((B_, cfg.top_k), dtype=torch.int32, device="cuda:0")
+    cache.moe_layer_decode(0, P.to_device(xs), y, torch.from_numpy(bias).cuda(), idx, None)
+    res = ost.decode(0, widen(xs), bias)
+    torch.cuda.synchronize()
+    assert idx.cpu().numpy().tolist() == res.idx.tolist()
+    assert rel_err(P.to_numpy(y), res.y).max() <= TOL["bf16"]
+    compare_traces_and_stats(cache, ost, [res.trace], cfg.expert_bytes)
+    cache.close()
+
+
 def test_deepseek_like_batched_shared_cache(torch, P):
     """Eight sequences decode together through one capacity-12 cache with two shared experts."""
     cfg = get_config("deepseek_like").with_(n_layers=1, n_seqs=8, n_steps=6)

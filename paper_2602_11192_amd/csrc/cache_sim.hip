@@ -10,7 +10,8 @@
 // Top-C membership of the requested experts without sorting; thread 0 adds the
 // K terms in request order.  Traces run in parallel across workgroups.  All
 // arithmetic is fp64 without contraction, in the order the recursion is
-// written, so the Top-C decisions agree with a plain CPU evaluation.
+// written, so the Top-C decisions agree with a plain CPU evaluation.  With at most 64 experts a single wave does
+// the same without LDS or barriers (cache_sim_wave_kernel below).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -81,6 +82,58 @@ __global__ void __launch_bounds__(1024) cache_sim_kernel(const int32_t* __restri
   }
 }
 
+// Up to 64 experts: one wave walks the trace, lane e holding expert e.  The values of the requested experts are read
+// with cross-lane moves (the requested id is wave-uniform), the rank is one ballot, and every lane carries the two
+// sums, so a token step needs neither LDS nor a barrier; the ids of the next token are fetched while the current one
+// is worked on.  Same arithmetic in the same order as the kernel above.
+__device__ __forceinline__ double readlane_f64(double v, int lane) {
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+  return __hiloint2double(hi, lo);
+}
+
+__global__ void __launch_bounds__(64) cache_sim_wave_kernel(const int32_t* __restrict__ idx, int T, int K, int E, int C,
+                                                            double gamma, const double* __restrict__ c1,
+                                                            double* __restrict__ out, int32_t* __restrict__ bad) {
+  const int trace = blockIdx.x;
+  const int lane = threadIdx.x;
+  const bool live = lane < E;
+  const int32_t* r = idx + (size_t)trace * T * K;
+  double c = live ? (c1 ? c1[(size_t)trace * E + lane] : (double)C / (double)E) : 0.0;
+  double ct = c;
+  double Gamma = 1.0, soft = 0.0, hard = 0.0;
+  const double k_over_c = (double)K / (double)C;
+  int invalid = 0;
+  int ids_next = (T > 0 && lane < K) ? r[lane] : 0;
+  for (int t = 0; t < T; ++t) {
+    const int ids = ids_next;                       // lane k: the k-th requested expert of token t
+    if (t + 1 < T && lane < K) ids_next = r[(size_t)(t + 1) * K + lane];
+    if (__ballot(lane < K && (ids < 0 || ids >= E)) != 0) { invalid = 1; break; }
+    int mine = 0;                                   // times this lane's expert is requested by the token
+    for (int k = 0; k < K; ++k) {
+      const int rk = __builtin_amdgcn_readlane(ids, k);
+      const double v = readlane_f64(ct, rk);
+      const bool ahead = live && (ct > v || (ct == v && lane < rk));
+      const int rank = __popcll(__ballot(ahead));
+      soft += 1.0 - readlane_f64(c, rk);
+      hard += rank < C ? 0.0 : 1.0;
+      mine += lane == rk ? 1 : 0;
+    }
+    const double Gamma_next = gamma * Gamma + k_over_c;
+    double cn = gamma * Gamma * c;
+    double ctn = gamma * ct;
+    for (int h = 0; h < mine; ++h) { cn += 1.0; ctn += 1.0; }
+    c = cn / Gamma_next;
+    ct = ctn;
+    Gamma = Gamma_next;
+  }
+  if (lane == 0) {
+    out[2 * trace] = soft;
+    out[2 * trace + 1] = hard;
+    bad[trace] = invalid;
+  }
+}
+
 }  // namespace
 
 extern "C" int moe_cache_sim_loss(const int32_t* idx_dev, int32_t n_traces, int32_t T, int32_t K, int32_t n_experts,
@@ -96,8 +149,14 @@ extern "C" int moe_cache_sim_loss(const int32_t* idx_dev, int32_t n_traces, int3
   if (!(gamma >= 0.0 && gamma <= 1.0)) return fail(MOE_ERR_INVALID_ARG, "gamma must be in [0,1]");
   if (n_traces == 0) return MOE_OK;
   const int threads = ((n_experts + 63) / 64) * 64;
-  hipLaunchKernelGGL(cache_sim_kernel, dim3((unsigned)n_traces), dim3(threads), 0, static_cast<hipStream_t>(hip_stream),
-                     idx_dev, T, K, n_experts, capacity, gamma, c1_dev, out_dev, flag_dev);
+  if (n_experts <= 64)
+    hipLaunchKernelGGL(cache_sim_wave_kernel, dim3((unsigned)n_traces), dim3(64), 0,
+                       static_cast<hipStream_t>(hip_stream), idx_dev, T, K, n_experts, capacity, gamma, c1_dev, out_dev,
+                       flag_dev);
+  else
+    hipLaunchKernelGGL(cache_sim_kernel, dim3((unsigned)n_traces), dim3(threads), 0,
+                       static_cast<hipStream_t>(hip_stream), idx_dev, T, K, n_experts, capacity, gamma, c1_dev, out_dev,
+                       flag_dev);
   const hipError_t err = hipGetLastError();
   if (err != hipSuccess) return fail(MOE_ERR_HIP, "cache_sim_kernel launch: %s", hipGetErrorString(err));
   return MOE_OK;

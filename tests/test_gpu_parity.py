@@ -405,7 +405,7 @@ def test_error_paths_on_device(torch, P):
 @pytest.mark.parametrize("E,K,C,T,gamma,init", [
     (64, 8, 16, 300, 0.9, "uniform"), (8, 2, 5, 257, 1.0, "uniform"), (16, 2, 10, 200, 0.0, "prefetch"),
     (1000, 6, 100, 120, 0.5, "uniform"), (64, 6, 12, 64, 0.97, "prefetch"), (5, 1, 1, 33, 0.3, "uniform"),
-    (130, 64, 65, 40, 0.8, "prefetch")])
+    (130, 64, 65, 40, 0.8, "prefetch"), (64, 64, 32, 20, 0.7, "uniform"), (33, 7, 33, 90, 0.6, "prefetch")])
 def test_cache_sim_loss_matches_oracle(torch, E, K, C, T, gamma, init):
     from paper_2602_11192_amd import binding as B
     n = 5

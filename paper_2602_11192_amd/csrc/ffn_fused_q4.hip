@@ -232,26 +232,23 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
   }
 }
 
-// Eight waves per workgroup unless the launch is large (measured: 24.0 against 27.7 us with 400 workgroups on the
-// Phi-like layer, 46.6 against 45.1 us with 896 on the Mixtral-like one).
-int pick_waves_q4(int d, int n_workgroups) {
+int pick_waves_q4(int d) {
 #ifdef MOE_Q4_FORCE_WAVES
   if (d % (64 * MOE_Q4_FORCE_WAVES) == 0) return MOE_Q4_FORCE_WAVES;
 #endif
-  if (d % 512 == 0 && n_workgroups <= 512) return 8;
-  return d % 256 == 0 ? 4 : 0;
+  return d % 512 == 0 ? 8 : d % 256 == 0 ? 4 : 0;
 }
 
 }  // namespace
 
 bool ffn_fused_q4_supported(int d, int f, int max_count) {
-  return max_count <= 16 && f % 32 == 0 && d >= 256 && pick_waves_q4(d, 1) != 0;
+  return max_count <= 16 && f % 32 == 0 && d >= 256 && pick_waves_q4(d) != 0;
 }
 
 hipError_t launch_ffn_fused_q4(hipStream_t s, const FfnArgs& a, KernelEvents ev) {
   if (a.g_max <= 0) return hipSuccess;
   dim3 grid(a.f / 32, a.g_max);
-  switch (pick_waves_q4(a.d, (a.f / 32) * a.g_max)) {
+  switch (pick_waves_q4(a.d)) {
     case 8:
       if (a.max_count == 1) launch_timed(ffn_fused_q4_kernel<8, true>, grid, dim3(512), 0, s, ev, a);
       else launch_timed(ffn_fused_q4_kernel<8, false>, grid, dim3(512), 0, s, ev, a);

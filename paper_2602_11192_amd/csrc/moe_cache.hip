@@ -40,6 +40,27 @@ int fail(int code, const char* fmt, ...) {
   va_end(ap);
   return code;
 }
+
+// Larger calls: the LDS-staged grouped GEMM (measured faster than the split-K streaming pair from 17 tokens
+// on: 119 against 139 us at 17 tokens, 138 against 190 us at 128 on the OLMoE-like layer, and faster than the
+// single-launch kernel from about 6 tokens: 90 against 96 us at 8, 123 against 136 us at 16).  The split-K
+// pair remains for small calls on shapes the single-launch kernel does not cover.
+FfnPlan plan_ffn(int pool_layout, int d, int f, int batch) {
+  FfnPlan p{};
+  p.tiled = pool_layout == MOE_LAYOUT_TILED;
+  p.q4 = pool_layout == MOE_LAYOUT_TILED_INT4;
+  p.fused = p.q4 ? batch <= 16 : (p.tiled && ffn_fused_supported(d, f, batch));
+  p.gemm = p.tiled && !p.fused && batch > fused_max_tokens(f);
+  return p;
+}
+
+hipError_t launch_ffn(hipStream_t s, int dtype, const FfnPlan& p, const FfnArgs& a, KernelEvents ke1, KernelEvents ke2) {
+  return p.q4 ? (p.fused ? launch_ffn_fused_q4(s, a, ke1) : launch_ffn_gemm_q4(s, a, ke1, ke2))
+         : p.fused ? launch_ffn_fused(s, a, ke1)
+         : p.gemm ? launch_ffn_gemm(s, a, ke1, ke2)
+         : p.tiled ? launch_ffn_tiled(s, a, ke1, ke2)
+                   : launch_ffn_rowmajor(s, dtype, a, ke1, ke2);
+}
 }  // namespace moe
 
 namespace {
@@ -656,15 +677,9 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   fa.g_max = (int)std::min<size_t>((size_t)batch * K, (size_t)c->P) + cf.n_shared;
   fa.max_count = batch;
   fa.t = c->t; fa.h = c->h; fa.o = c->o;
-  const bool tiled = cf.pool_layout == MOE_LAYOUT_TILED;
-  const bool q4w = cf.pool_layout == MOE_LAYOUT_TILED_INT4;
-  const bool fused = q4w ? batch <= 16 : (tiled && ffn_fused_supported(d, cf.d_ff, batch));
+  const FfnPlan plan = plan_ffn(cf.pool_layout, d, cf.d_ff, batch);
+  const bool fused = plan.fused;
   fa.fused = fused ? 1 : 0;
-  // Larger calls: the LDS-staged grouped GEMM (measured faster than the split-K streaming pair from 17 tokens
-  // on: 119 against 139 us at 17 tokens, 138 against 190 us at 128 on the OLMoE-like layer, and faster than the
-  // single-launch kernel from about 6 tokens: 90 against 96 us at 8, 123 against 136 us at 16).  The split-K
-  // pair remains for small calls on shapes the single-launch kernel does not cover.
-  const bool gemm = tiled && !fused && batch > fused_max_tokens(cf.d_ff);
   const KernelEvents ke1 = ps ? ps->gate_up : KernelEvents{}, ke2 = ps ? ps->down : KernelEvents{};
 
   // Experts that were already resident: their FFN starts right behind the cache
@@ -674,11 +689,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   fa.pool = in_kernel ? c->pool_dev[layer] : nullptr;
   fa.fetch = in_kernel ? 1 : 0;
   fa.pass = in_kernel ? 2 : 0;
-  HIPCHK(q4w ? (fused ? launch_ffn_fused_q4(s, fa, ke1) : launch_ffn_gemm_q4(s, fa, ke1, ke2))
-         : fused ? launch_ffn_fused(s, fa, ke1)
-         : gemm ? launch_ffn_gemm(s, fa, ke1, ke2)
-         : tiled ? launch_ffn_tiled(s, fa, ke1, ke2)
-                 : launch_ffn_rowmajor(s, cf.dtype, fa, ke1, ke2));
+  HIPCHK(launch_ffn(s, cf.dtype, plan, fa, ke1, ke2));
 
   HIPCHK(hipEventSynchronize(c->ev_mail));
   const uint32_t got = __atomic_load_n(&c->mailbox->seq, __ATOMIC_ACQUIRE);
@@ -693,12 +704,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
     HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0));
     c->copies_pending = false;
     fa.pass = 1;
-    HIPCHK(q4w ? (fused ? launch_ffn_fused_q4(s, fa, KernelEvents{})
-                        : launch_ffn_gemm_q4(s, fa, KernelEvents{}, KernelEvents{}))
-           : fused ? launch_ffn_fused(s, fa, KernelEvents{})
-           : gemm ? launch_ffn_gemm(s, fa, KernelEvents{}, KernelEvents{})
-           : tiled ? launch_ffn_tiled(s, fa, KernelEvents{}, KernelEvents{})
-                   : launch_ffn_rowmajor(s, cf.dtype, fa, KernelEvents{}, KernelEvents{}));
+    HIPCHK(launch_ffn(s, cf.dtype, plan, fa, KernelEvents{}, KernelEvents{}));
   }
   if (ps) {
     ps->used = true; ps->mixed = mb.n_miss > 0; ps->fused = fused;

@@ -134,6 +134,10 @@ hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 bool ffn_fused_q4_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused_q4(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 hipError_t launch_ffn_gemm_q4(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
+// Which expert-FFN kernels run a call of `batch` tokens on experts of the given layout and shape.
+struct FfnPlan { bool fused, gemm, tiled, q4; };
+FfnPlan plan_ffn(int pool_layout, int d, int f, int batch);
+hipError_t launch_ffn(hipStream_t s, int dtype, const FfnPlan& p, const FfnArgs& a, KernelEvents ke1, KernelEvents ke2);
 hipError_t launch_combine_chunks(hipStream_t s, const float* o_part, const float* wpair, const int32_t* pos_of,
                                  int B, int KS, int d, int n_chunks, void* y);
 hipError_t launch_combine(hipStream_t s, int dtype, const float* o, const float* wpair, const int32_t* pos_of,

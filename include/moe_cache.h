@@ -318,6 +318,34 @@ int moe_cache_sim_loss(const int32_t* idx_dev, int32_t n_traces, int32_t T, int3
                        int32_t capacity, double gamma, const double* c1_dev, double* out_dev, int32_t* flag_dev,
                        void* hip_stream);
 
+/*
+ * For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): moe_layer_decode() for a layer whose experts ALL sit in device memory, without a cache
+ * object.  The call allocates nothing: the tables and partial sums its kernels need live in one device array of
+ * MOE_NOALLOC_SCRATCH_BYTES that the library holds on every GPU it runs on until the process ends.
+ *   layer      host; shape of the layer and device pointers to its parameters (all borrowed for the call):
+ *              router_w [E][d], experts [E] expert blocks in `pool_layout` (expert e at byte e *
+ *              moe_expert_block_bytes()), shared_w [n_shared] blocks or NULL iff n_shared == 0
+ *   other arguments as for moe_layer_decode; the device is the calling thread's current device.
+ * Outputs equal those of moe_layer_decode on a cache of capacity E preloaded with experts 0..E-1 in that order.
+ * Nothing is counted or traced.  A batch whose tables and partial sums exceed the array is rejected with
+ * MOE_ERR_UNSUPPORTED (the message names the bytes needed).  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams without ordering, different threads) race.
+ */
+#define MOE_NOALLOC_SCRATCH_BYTES (32u << 20)
+typedef struct {
+  int32_t n_experts, n_shared, top_k, d_model, d_ff;
+  int32_t dtype;        /* MOE_DTYPE_*                                                          */
+  int32_t norm_topk;    /* as in moe_cache_config_t                                             */
+  int32_t pool_layout;  /* MOE_LAYOUT_*                                                         */
+  const void* router_w; /* device                                                               */
+  const void* experts;  /* device                                                               */
+  const void* shared_w; /* device or NULL                                                       */
+} moe_resident_layer_t;
+int moe_layer_decode_resident_noalloc(const moe_resident_layer_t* layer, const void* x_dev,
+                                      const float* logit_bias_dev, int32_t batch, void* y_dev,
+                                      int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
+
 /* Text of the last error on this thread ("" if none). */
 const char* moe_last_error(void);
 

@@ -31,7 +31,8 @@ MOE_FETCH_COPY_ENGINE, MOE_FETCH_IN_KERNEL = 0, 1
 EXPORTS = ["moe_expert_bytes", "moe_expert_block_bytes", "moe_pack_expert", "moe_pack_expert_int4", "moe_cache_create", "moe_cache_destroy", "moe_cache_reset",
            "moe_cache_prefill_pins", "moe_layer_decode", "moe_layer_prefill", "moe_cache_stats", "moe_cache_read_trace",
            "moe_cache_resident", "moe_cache_set_profiling", "moe_cache_timing", "moe_probe_stream",
-           "moe_cache_sim_loss", "moe_pooled_prefetch_set", "moe_last_error", "moe_version"]
+           "moe_cache_sim_loss", "moe_pooled_prefetch_set", "moe_layer_decode_resident_noalloc", "moe_last_error",
+           "moe_version"]
 
 
 class moe_cache_config_t(C.Structure):
@@ -61,6 +62,12 @@ class moe_timing_t(C.Structure):
                 ("route_launches", C.c_uint64), ("route_ms", C.c_double),
                 ("fetch_launches", C.c_uint64), ("fetch_bytes", C.c_uint64), ("fetch_ms", C.c_double),
                 ("copies", C.c_uint64), ("copy_bytes", C.c_uint64), ("copy_ms", C.c_double)]
+
+
+class moe_resident_layer_t(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_experts", "n_shared", "top_k", "d_model", "d_ff", "dtype", "norm_topk",
+                                         "pool_layout")] + [("router_w", C.c_void_p), ("experts", C.c_void_p),
+                                                            ("shared_w", C.c_void_p)]
 
 
 class MoeError(RuntimeError):
@@ -96,6 +103,7 @@ def _load():
     lib.moe_probe_stream.argtypes = [vp, vp, C.c_uint64, i32, i32, vp, C.POINTER(C.c_double)]
     lib.moe_cache_sim_loss.argtypes = [vp, i32, i32, i32, i32, i32, C.c_double, vp, vp, vp, vp]
     lib.moe_pooled_prefetch_set.argtypes = [vp, i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+    lib.moe_layer_decode_resident_noalloc.argtypes = [C.POINTER(moe_resident_layer_t), vp, vp, i32, vp, vp, vp, vp]
     lib.moe_last_error.restype = C.c_char_p
     lib.moe_version.restype = C.c_char_p
     for name in EXPORTS:
@@ -180,6 +188,17 @@ def moe_cache_sim_loss(idx, n_experts: int, capacity: int, gamma: float, c1=None
     _check(lib.moe_cache_sim_loss(_ptr(idx), n, T, K, n_experts, capacity, float(gamma), _ptr(c1), _ptr(out),
                                   _ptr(flag), _stream(stream)))
     return out, flag
+
+
+def moe_layer_decode_resident_noalloc(*, n_experts, top_k, d_model, d_ff, dtype, pool_layout, router_w, experts, x, y,
+                                      shared_w=None, n_shared=0, norm_topk=1, logit_bias=None, topk_idx=None,
+                                      topk_w=None, stream=None):
+    """One MoE block over device-resident experts through the entry point that allocates nothing.
+    router_w [E, d], experts (flat, E blocks), x, y [B, d]: device tensors."""
+    layer = moe_resident_layer_t(n_experts, n_shared, top_k, d_model, d_ff, dtype, norm_topk, pool_layout,
+                                 _ptr(router_w), _ptr(experts), _ptr(shared_w))
+    _check(lib.moe_layer_decode_resident_noalloc(C.byref(layer), _ptr(x), _ptr(logit_bias), x.shape[0], _ptr(y),
+                                                 _ptr(topk_idx), _ptr(topk_w), _stream(stream)))
 
 
 def _ptr(t):

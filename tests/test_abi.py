@@ -146,3 +146,21 @@ def test_pooled_prefetch_set_hand_example_and_oracle(B):
         assert B.moe_pooled_prefetch_set(sc, cap) == oracle.pooled_prefetch_set(sc, cap)
     with pytest.raises(B.MoeError):
         B.moe_pooled_prefetch_set(scores, 0)
+
+
+def test_noalloc_entry_point_validates_before_touching_the_gpu(B):
+    """Shapes, null pointers and batches beyond the fixed device array are refused on the host."""
+    def call(batch=1, x=0x1000, y=0x2000, **kw):
+        f = dict(n_experts=16, n_shared=0, top_k=4, d_model=256, d_ff=128, dtype=B.MOE_DTYPE_BF16, norm_topk=1,
+                 pool_layout=B.MOE_LAYOUT_TILED, router_w=0x3000, experts=0x4000, shared_w=None)
+        f.update(kw)
+        layer = B.moe_resident_layer_t(**f)
+        return B.lib.moe_layer_decode_resident_noalloc(C.byref(layer), x, None, batch, y, None, None, None)
+    assert call(top_k=0) == B.MOE_ERR_INVALID_ARG
+    assert call(x=None) == B.MOE_ERR_INVALID_ARG
+    assert call(experts=None) == B.MOE_ERR_INVALID_ARG
+    assert call(n_shared=1) == B.MOE_ERR_INVALID_ARG
+    assert call(d_ff=100) == B.MOE_ERR_UNSUPPORTED
+    assert call(batch=0) == B.MOE_ERR_INVALID_ARG
+    assert call(batch=1 << 16) == B.MOE_ERR_UNSUPPORTED and "scratch" in B.moe_last_error()
+    assert C.sizeof(B.moe_resident_layer_t) == 8 * 4 + 3 * 8

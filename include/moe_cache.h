@@ -25,9 +25,12 @@
  *   - Streams are passed as void* holding a hipStream_t (NULL = the null
  *     stream).  Kernels of a call are enqueued on the caller's stream; expert
  *     copies run on a stream the library owns.  A call returns once its work
- *     is enqueued, after a short host wait for the miss list of that call.
+ *     is enqueued; calls that may have to issue copies or to split (see
+ *     moe_layer_decode) first wait on the host for the miss list of that call.
  *     Results are valid after the caller synchronises the stream.
- *   - A cache object is not thread-safe; use one thread per cache.
+ *   - A cache object is not thread-safe; use one thread per cache.  All calls on
+ *     one cache share its tables and scratch: issue them on ONE stream, or order
+ *     the streams yourself (events) so that calls never overlap on the device.
  */
 #ifndef MOE_CACHE_H
 #define MOE_CACHE_H
@@ -154,6 +157,9 @@ typedef struct {
   uint64_t fetch_launches; /* in-kernel fetch: expert-FFN launches that also fetched experts */
   uint64_t fetch_bytes;  /* bytes those launches brought in over PCIe                        */
   double fetch_ms;       /* their summed duration (fetch and compute overlap inside them)   */
+  uint64_t decode_single_launches; /* calls without a miss that ran as ONE launch (router, gating, lookups,
+                            expert FFN and combine together)                                  */
+  double decode_single_ms; /* summed duration of those launches                              */
   uint64_t copies;       /* expert copies timed                                             */
   uint64_t copy_bytes;   /* bytes moved by them                                             */
   double copy_ms;        /* summed duration of the copy batches on the copy stream          */
@@ -185,6 +191,8 @@ int moe_pack_expert_int4(const uint8_t* codes, const uint16_t* scales, void* dst
                          int32_t d_ff);
 
 /*
+ * The expert cache of section 2, "Expert Offloading Systems", and section 3.2: per layer, C of the E experts
+ * are resident in device memory, the others stay in pinned host memory and are fetched on demand.
  * Create a cache for a layer stack: allocates L * (C + staging_buffers) expert
  * buffers on the device, the per-layer cache tables, scratch for max_batch
  * tokens and a copy stream.  All caches start empty.
@@ -209,8 +217,10 @@ int moe_cache_reset(moe_cache_t* cache, int32_t layer, int32_t clear_stats, void
  * Equivalent to n lookups in list order that are counted as pin_loads rather
  * than hits or misses; entries already resident are only refreshed; loaded
  * experts remain evictable.  expert_ids: host, n distinct ids in [0,E), n <= C.
- * The copies run on the library's copy stream; later calls on any stream are
- * ordered after them.
+ * The copies run on the library's copy stream; `hip_stream` is made to wait for
+ * them before the call returns, so later work on that stream sees the experts.
+ * Paper anchor for the capacity-C cache this fills: section 2, "Expert Offloading
+ * Systems" (a fixed number of experts per layer resident in device memory).
  */
 int moe_cache_prefill_pins(moe_cache_t* cache, int32_t layer, const int32_t* expert_ids,
                            int32_t n, void* hip_stream);
@@ -227,6 +237,10 @@ int moe_cache_prefill_pins(moe_cache_t* cache, int32_t layer, const int32_t* exp
  * is executed as consecutive waves of tokens (the batch is halved until every wave
  * fits; one token always fits); routing, hits, misses, evictions and outputs are the
  * same as for the unsplit call, only slower.
+ * Host waits: none for batch 1, or for a cache that holds every expert (C >= E), on bf16 experts in the tiled
+ * layout with in-kernel fetch (router, gating, lookups and the expert FFN are then one launch, the combine a
+ * second one); every other call waits for the device to report the miss list (copy-engine fetch) or whether
+ * it has to be split (batched calls on a constrained cache).
  * Errors: INVALID_ARG (null x/y, batch < 1 or > max_batch, layer out of range), HIP, TIMEOUT.
  */
 int moe_layer_decode(moe_cache_t* cache, int32_t layer, const void* x_dev,
@@ -253,13 +267,19 @@ int moe_pooled_prefetch_set(const float* scores, int32_t n_seqs, int32_t n_exper
  * resident are read from their buffers, every other selected expert is read straight from the pinned host pool
  * by the kernels and is NOT inserted; recency, counts, the trace and hits/misses are left untouched, so a one-off
  * scan over a long prompt does not flush the cache.  Counted as stream_loads / bytes_streamed.
- * Arguments as for moe_layer_decode; n_tokens <= max_batch.  Needs the tiled bf16 layout (MOE_ERR_UNSUPPORTED
- * otherwise) and a device-visible pinned expert_pool.
+ * Arguments as for moe_layer_decode; n_tokens <= max_batch.  Needs a tiled layout, bf16 or INT4
+ * (MOE_ERR_UNSUPPORTED otherwise) and a device-visible pinned expert_pool.
  */
 int moe_layer_prefill(moe_cache_t* cache, int32_t layer, const void* x_dev, const float* logit_bias_dev,
                       int32_t n_tokens, void* y_dev, int32_t* topk_idx_dev, float* topk_w_dev, void* hip_stream);
 
-/* Counters of one layer (layer = -1: summed over layers).  Host-side, no device wait. */
+/*
+ * Counters of one layer (layer = -1: summed over layers).  `misses` is the N_miss of the paper's latency model
+ * (Eq. 4: decode time = compute time + N_miss x transfer time), and, as appendix C.1 notes, the number of cache
+ * misses equals the number of host->device expert transfers: bytes_h2d = (misses + pin_loads) x block bytes.
+ * Calls that did not wait for the device counted their hits and misses there: the call waits for the device's
+ * enqueued work when such calls were made since the cache was created.
+ */
 int moe_cache_stats(const moe_cache_t* cache, int32_t layer, moe_cache_stats_t* out);
 
 /*

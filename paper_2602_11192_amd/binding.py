@@ -61,6 +61,7 @@ class moe_timing_t(C.Structure):
                 ("ffn_fused_launches", C.c_uint64), ("ffn_fused_ms", C.c_double),
                 ("route_launches", C.c_uint64), ("route_ms", C.c_double),
                 ("fetch_launches", C.c_uint64), ("fetch_bytes", C.c_uint64), ("fetch_ms", C.c_double),
+                ("decode_single_launches", C.c_uint64), ("decode_single_ms", C.c_double),
                 ("copies", C.c_uint64), ("copy_bytes", C.c_uint64), ("copy_ms", C.c_double)]
 
 

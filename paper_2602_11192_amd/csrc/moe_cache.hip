@@ -76,6 +76,7 @@ constexpr int kProfSlots = 512;
 struct ProfSlot {
   KernelEvents route, gate_up, down;   // attached to the dispatches of the three main kernels of a call
   bool used = false;
+  bool single = false; // the call was one launch (router to combine, timed by `gate_up`); its record is in the call log
   bool mixed = false;  // the call also fetched experts: its resident-pass FFN covers only part of the K experts
   bool fused = false;  // the call used the single-launch decode FFN (timed by `gate_up`)
   uint64_t fetched = 0; // bytes that launch read from the host pool (in-kernel fetch)
@@ -99,7 +100,15 @@ struct moe_cache {
 
   char* buffers = nullptr;        // [L][P] expert blocks
   char* table_mem = nullptr;      // all LayerState arrays
-  std::vector<LayerState> layers;
+  std::vector<LayerState> layers;      // [L][2]: two copies of every layer's table (see cur)
+  std::vector<uint8_t> cur;            // [L] which copy is current; the single-launch decode reads it and writes the other
+  unsigned long long* dev_stats = nullptr;   // [L][4] hits, misses, evictions counted on the device by calls without a host wait
+  bool dev_stats_used = false;
+  size_t layer_stride = 0;             // bytes between the tables (and device counters) of consecutive layers
+  char* router_packed = nullptr;       // [L] router matrices in operand order, for the single-launch decode
+  bool single_ok = false;              // the single-launch decode kernel covers this cache's shape and policy
+  int single_max_batch = 0;
+  Mailbox* call_log = nullptr;         // pinned, [kProfSlots]: call records of launches being timed
   CallTables t{};
   char* call_mem = nullptr;
   void* h = nullptr;
@@ -130,6 +139,8 @@ struct moe_cache {
 };
 
 namespace {
+
+LayerState& state_of(moe_cache* c, int layer) { return c->layers[(size_t)layer * 2 + c->cur[layer]]; }
 
 struct DeviceGuard {
   int prev = -1;
@@ -223,9 +234,11 @@ void free_all(moe_cache* c) {
   if (c->buffers) (void)hipFree(c->buffers);
   if (c->table_mem) (void)hipFree(c->table_mem);
   if (c->call_mem) (void)hipFree(c->call_mem);
+  if (c->router_packed) (void)hipFree(c->router_packed);
   if (c->h) (void)hipFree(c->h);
   if (c->o) (void)hipFree(c->o);
   if (c->host_mem) (void)hipHostFree(c->host_mem);
+  if (c->call_log) (void)hipHostFree(c->call_log);
   delete c;
 }
 
@@ -280,6 +293,20 @@ int drain_prof_slot(moe_cache* c, ProfSlot& p) {
   if (!p.used) return MOE_OK;
   HIPCHK(hipEventSynchronize(p.fused ? p.gate_up.stop : p.down.stop));
   float a = 0.f, b = 0.f, r = 0.f;
+  if (p.single) {       // one launch from the router to the combine; its call record sits in the log
+    HIPCHK(hipEventElapsedTime(&a, p.gate_up.start, p.gate_up.stop));
+    const Mailbox mb = c->call_log[&p - c->prof.data()];
+    if (mb.n_miss > 0) {
+      c->timing.fetch_launches += 1;
+      c->timing.fetch_bytes += (uint64_t)mb.n_miss * c->expert_bytes;
+      c->timing.fetch_ms += a;
+    } else {
+      c->timing.decode_single_ms += a;
+      c->timing.decode_single_launches += 1;
+    }
+    p.used = false;
+    return MOE_OK;
+  }
   HIPCHK(hipEventElapsedTime(&r, p.route.start, p.route.stop));
   HIPCHK(hipEventElapsedTime(&a, p.gate_up.start, p.gate_up.stop));
   if (!p.fused) HIPCHK(hipEventElapsedTime(&b, p.down.start, p.down.stop));
@@ -455,33 +482,40 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
 
   CREATE_CHK(hipMalloc(&c->buffers, (size_t)L * P * c->expert_bytes), MOE_ERR_HIP);
 
-  // ---- per-layer tables ----
-  size_t per_layer = 0;
-  const size_t o_tick = per_layer; per_layer += align_up((size_t)C * 8, 16);
+  // ---- per-layer tables: two copies of everything a decode call rewrites, one score array, one trace ----
+  size_t ver = 0;
+  const size_t o_tick = ver; ver += align_up((size_t)C * 8, 16);
+  const size_t o_scal = ver; ver += align_up((size_t)SC_COUNT * 8, 16);
+  const size_t o_ein = ver; ver += align_up((size_t)C * 4, 16);
+  const size_t o_bos = ver; ver += align_up((size_t)C * 4, 16);
+  const size_t o_free = ver; ver += align_up((size_t)P * 4, 16);
+  const size_t o_zom = ver; ver += align_up((size_t)P * 4, 16);
+  const size_t o_used = ver; ver += align_up((size_t)P * 4, 16);
+  size_t per_layer = 2 * ver;
   const size_t o_score = per_layer; per_layer += align_up((size_t)E * 8, 16);
-  const size_t o_scal = per_layer; per_layer += align_up((size_t)SC_COUNT * 8, 16);
-  const size_t o_ein = per_layer; per_layer += align_up((size_t)C * 4, 16);
-  const size_t o_bos = per_layer; per_layer += align_up((size_t)C * 4, 16);
-  const size_t o_free = per_layer; per_layer += align_up((size_t)P * 4, 16);
-  const size_t o_zom = per_layer; per_layer += align_up((size_t)P * 4, 16);
-  const size_t o_used = per_layer; per_layer += align_up((size_t)P * 4, 16);
+  const size_t o_dstat = per_layer; per_layer += 32;
   const size_t o_trace = per_layer; per_layer += align_up((size_t)cfg->trace_capacity * sizeof(moe_trace_rec_t), 16);
   CREATE_CHK(hipMalloc(&c->table_mem, per_layer * L), MOE_ERR_HIP);
   CREATE_CHK(hipMemset(c->table_mem, 0, per_layer * L), MOE_ERR_HIP);
-  c->layers.resize(L);
-  for (int l = 0; l < L; ++l) {
-    char* b = c->table_mem + per_layer * l;
-    LayerState& s = c->layers[l];
-    s.tick = reinterpret_cast<uint64_t*>(b + o_tick);
-    s.score = reinterpret_cast<double*>(b + o_score);
-    s.scalars = reinterpret_cast<int64_t*>(b + o_scal);
-    s.expert_in = reinterpret_cast<int32_t*>(b + o_ein);
-    s.buf_of_slot = reinterpret_cast<int32_t*>(b + o_bos);
-    s.free_buf = reinterpret_cast<int32_t*>(b + o_free);
-    s.zombie = reinterpret_cast<int32_t*>(b + o_zom);
-    s.used_stamp = reinterpret_cast<uint32_t*>(b + o_used);
-    s.trace = cfg->trace_capacity > 0 ? reinterpret_cast<moe_trace_rec_t*>(b + o_trace) : nullptr;
-  }
+  c->layers.resize((size_t)L * 2);
+  c->cur.assign(L, 0);
+  c->dev_stats = reinterpret_cast<unsigned long long*>(c->table_mem + o_dstat);   // layer l: + l * per_layer bytes
+  c->layer_stride = per_layer;
+  for (int l = 0; l < L; ++l)
+    for (int v = 0; v < 2; ++v) {
+      char* b = c->table_mem + per_layer * l;
+      char* bv = b + ver * v;
+      LayerState& s = c->layers[(size_t)l * 2 + v];
+      s.tick = reinterpret_cast<uint64_t*>(bv + o_tick);
+      s.scalars = reinterpret_cast<int64_t*>(bv + o_scal);
+      s.expert_in = reinterpret_cast<int32_t*>(bv + o_ein);
+      s.buf_of_slot = reinterpret_cast<int32_t*>(bv + o_bos);
+      s.free_buf = reinterpret_cast<int32_t*>(bv + o_free);
+      s.zombie = reinterpret_cast<int32_t*>(bv + o_zom);
+      s.used_stamp = reinterpret_cast<uint32_t*>(bv + o_used);
+      s.score = reinterpret_cast<double*>(b + o_score);
+      s.trace = cfg->trace_capacity > 0 ? reinterpret_cast<moe_trace_rec_t*>(b + o_trace) : nullptr;
+    }
 
   // ---- per-call scratch ----
   size_t cm = 0;
@@ -557,12 +591,22 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
       }
     }
   }
+  if (cfg->pool_layout == MOE_LAYOUT_TILED && cfg->fetch_mode == MOE_FETCH_IN_KERNEL && !c->pool_dev.empty()) {
+    for (int b = 1; b <= std::min(Bm, fused_max_tokens(cfg->d_ff)); ++b)
+      if (decode_single_supported(cfg->policy, E, C, P, cfg->n_shared, K, cfg->d_model, cfg->d_ff, b)) c->single_max_batch = b;
+      else break;
+    c->single_ok = c->single_max_batch >= 1;
+  }
+  if (c->single_ok) {
+    CREATE_CHK(hipMalloc(&c->router_packed, router_packed_bytes(E, cfg->d_model) * L), MOE_ERR_HIP);
+    CREATE_CHK(launch_pack_router(nullptr, weights->router_w, c->router_packed, E, cfg->d_model, L), MOE_ERR_HIP);
+  }
   CREATE_CHK(hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking), MOE_ERR_HIP);
   CREATE_CHK(hipEventCreateWithFlags(&c->ev_mail, hipEventDisableTiming), MOE_ERR_HIP);
   CREATE_CHK(hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming), MOE_ERR_HIP);
   CREATE_CHK(hipEventCreateWithFlags(&c->ev_order, hipEventDisableTiming), MOE_ERR_HIP);
 
-  for (int l = 0; l < L; ++l) CREATE_CHK(launch_reset(nullptr, c->layers[l], E, C, P, 1), MOE_ERR_HIP);
+  for (int l = 0; l < L; ++l) CREATE_CHK(launch_reset(nullptr, state_of(c, l), E, C, P, 1, nullptr), MOE_ERR_HIP);
   CREATE_CHK(hipStreamSynchronize(nullptr), MOE_ERR_HIP);
 #undef CREATE_CHK
   *out = c;
@@ -586,7 +630,8 @@ int moe_cache_reset(moe_cache_t* c, int32_t layer, int32_t clear_stats, void* hi
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? c->cfg.n_layers : layer + 1;
   for (int l = l0; l < l1; ++l) {
-    HIPCHK(launch_reset(s, c->layers[l], c->cfg.n_experts, c->C, c->P, clear_stats ? 1 : 0));
+    unsigned long long* ds = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(c->dev_stats) + c->layer_stride * l);
+    HIPCHK(launch_reset(s, state_of(c, l), c->cfg.n_experts, c->C, c->P, clear_stats ? 1 : 0, clear_stats ? ds : nullptr));
     if (clear_stats) c->stats[l] = moe_cache_stats_t{};
   }
   return MOE_OK;
@@ -615,7 +660,7 @@ int moe_cache_prefill_pins(moe_cache_t* c, int32_t layer, const int32_t* expert_
   a.trace_cap = c->cfg.trace_capacity; a.seq = ++c->seq; a.pin_ids = c->pin_ids;
   a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
   if (c->copies_pending) { HIPCHK(hipStreamWaitEvent(s, c->ev_copy, 0)); c->copies_pending = false; }
-  HIPCHK(launch_pin(s, c->layers[layer], c->t, a));
+  HIPCHK(launch_pin(s, state_of(c, layer), c->t, a));
   int rc = wait_mailbox(c, s, a.seq);
   if (rc != MOE_OK) return rc;
   const Mailbox mb = *c->mailbox;
@@ -659,12 +704,50 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
   ra.user_idx = topk_idx_dev; ra.user_w = topk_w_dev;
   ra.arrive = c->arrive;
 
+  // One launch up to the combine, and no host wait: batch 1 (a single token's experts always fit), or a cache
+  // that holds every expert (nothing is ever evicted) - the two cases in which a call cannot run out of spare
+  // buffers - on the shapes the single-launch kernel covers.
+  if (c->single_ok && batch <= c->single_max_batch && (batch == 1 || c->C >= E)) {
+    RoutedArgs q{};
+    q.r = ra;
+    q.router_packed = c->router_packed + router_packed_bytes(E, d) * layer;
+    q.st_in = state_of(c, layer);
+    q.st_out = c->layers[(size_t)layer * 2 + (c->cur[layer] ^ 1)];
+    CacheCallArgs& a = q.a;
+    a.mode = 0; a.B = batch; a.K = K; a.KS = KS; a.E = E; a.C = c->C; a.P = c->P; a.n_shared = cf.n_shared;
+    a.row0 = row0;
+    a.policy = cf.policy; a.gamma = cf.gamma; a.trace_cap = cf.trace_capacity; a.seq = ++c->seq;
+    a.pin_ids = nullptr; a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
+    q.dev_stats = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(c->dev_stats) + c->layer_stride * layer);
+    q.log = ps ? c->call_log + (ps - c->prof.data()) : nullptr;
+    FfnArgs fa{};
+    fa.x = x_dev;
+    fa.buffers = c->buffers + (size_t)layer * c->P * c->expert_bytes;
+    fa.shared = cf.n_shared ? static_cast<const char*>(c->w.shared_w) + (size_t)layer * cf.n_shared * c->expert_bytes
+                            : nullptr;
+    fa.expert_bytes = c->expert_bytes;
+    fa.P = c->P; fa.d = d; fa.f = cf.d_ff; fa.KS = KS;
+    fa.g_max = (int)std::min<size_t>((size_t)batch * K, (size_t)c->P) + cf.n_shared;
+    fa.max_count = batch;
+    fa.t = c->t; fa.h = c->h; fa.o = c->o;
+    fa.fused = 1; fa.pass = 2;
+    fa.pool = c->pool_dev[layer];
+    fa.fetch = 1;
+    HIPCHK(launch_decode_single(s, fa, q, ps ? ps->gate_up : KernelEvents{}));
+    HIPCHK(launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev));
+    c->cur[layer] ^= 1;
+    c->dev_stats_used = true;
+    c->stats[layer].lookups += (uint64_t)batch * K;
+    if (ps) { ps->used = true; ps->single = true; ps->fused = true; ps->mixed = false; ps->fetched = 0; }
+    return MOE_OK;
+  }
+
   CacheCallArgs a{};
   a.mode = 0; a.B = batch; a.K = K; a.KS = KS; a.E = E; a.C = c->C; a.P = c->P; a.n_shared = cf.n_shared;
   a.row0 = row0;
   a.policy = cf.policy; a.gamma = cf.gamma; a.trace_cap = cf.trace_capacity; a.seq = ++c->seq;
   a.pin_ids = nullptr; a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
-  HIPCHK(launch_route_cache(s, cf.dtype, ra, c->layers[layer], c->t, a, ps ? ps->route : KernelEvents{}));
+  HIPCHK(launch_route_cache(s, cf.dtype, ra, state_of(c, layer), c->t, a, ps ? ps->route : KernelEvents{}));
   HIPCHK(hipEventRecord(c->ev_mail, s));
 
   FfnArgs fa{};
@@ -707,7 +790,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
     HIPCHK(launch_ffn(s, cf.dtype, plan, fa, KernelEvents{}, KernelEvents{}));
   }
   if (ps) {
-    ps->used = true; ps->mixed = mb.n_miss > 0; ps->fused = fused;
+    ps->used = true; ps->single = false; ps->mixed = mb.n_miss > 0; ps->fused = fused;
     ps->fetched = in_kernel ? (uint64_t)mb.n_miss * c->expert_bytes : 0;
   }
   HIPCHK(fused ? launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev)
@@ -801,7 +884,7 @@ int moe_layer_prefill(moe_cache_t* c, int32_t layer, const void* x_dev, const fl
   a.mode = 2; a.B = n_tokens; a.K = K; a.KS = KS; a.E = E; a.C = c->C; a.P = c->P; a.n_shared = cf.n_shared;
   a.policy = cf.policy; a.gamma = cf.gamma; a.trace_cap = 0; a.seq = ++c->seq;
   a.pin_ids = nullptr; a.mailbox = c->mailbox; a.miss_list = c->miss_list; a.max_miss = c->max_miss;
-  HIPCHK(launch_route_cache(s, cf.dtype, ra, c->layers[layer], c->t, a, KernelEvents{}));
+  HIPCHK(launch_route_cache(s, cf.dtype, ra, state_of(c, layer), c->t, a, KernelEvents{}));
   HIPCHK(hipEventRecord(c->ev_mail, s));
 
   FfnArgs fa{};
@@ -834,12 +917,23 @@ int moe_layer_prefill(moe_cache_t* c, int32_t layer, const void* x_dev, const fl
 int moe_cache_stats(const moe_cache_t* c, int32_t layer, moe_cache_stats_t* out) {
   if (!c || !out) return fail(MOE_ERR_INVALID_ARG, "null argument");
   if (layer < -1 || layer >= c->cfg.n_layers) return fail(MOE_ERR_INVALID_ARG, "layer %d out of range", layer);
+  const int L = c->cfg.n_layers;
+  // calls that did not wait for the device counted their hits, misses and evictions there
+  std::vector<unsigned long long> dev((size_t)L * 4, 0ull);
+  if (c->dev_stats_used) {
+    DeviceGuard guard;
+    HIPCHK(guard.enter(c->device));
+    HIPCHK(hipDeviceSynchronize());
+    HIPCHK(hipMemcpy2D(dev.data(), 32, c->dev_stats, c->layer_stride, 32, L, hipMemcpyDeviceToHost));
+  }
   moe_cache_stats_t s{};
-  const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? c->cfg.n_layers : layer + 1;
+  const int l0 = layer < 0 ? 0 : layer, l1 = layer < 0 ? L : layer + 1;
   for (int l = l0; l < l1; ++l) {
     const moe_cache_stats_t& v = c->stats[l];
-    s.lookups += v.lookups; s.hits += v.hits; s.misses += v.misses;
-    s.evictions += v.evictions; s.pin_loads += v.pin_loads; s.bytes_h2d += v.bytes_h2d;
+    const unsigned long long* dv = &dev[(size_t)l * 4];
+    s.lookups += v.lookups; s.hits += v.hits + dv[0]; s.misses += v.misses + dv[1];
+    s.evictions += v.evictions + dv[2]; s.pin_loads += v.pin_loads;
+    s.bytes_h2d += v.bytes_h2d + dv[1] * c->expert_bytes;
     s.stream_loads += v.stream_loads; s.bytes_streamed += v.bytes_streamed;
   }
   *out = s;
@@ -855,9 +949,9 @@ int moe_cache_read_trace(moe_cache_t* c, int32_t layer, moe_trace_rec_t* host_ou
   HIPCHK(guard.enter(c->device));
   HIPCHK(hipDeviceSynchronize());
   int64_t total = 0;
-  HIPCHK(hipMemcpy(&total, c->layers[layer].scalars + SC_TRACE_N, 8, hipMemcpyDeviceToHost));
+  HIPCHK(hipMemcpy(&total, state_of(c, layer).scalars + SC_TRACE_N, 8, hipMemcpyDeviceToHost));
   int64_t n = std::min<int64_t>(std::min<int64_t>(total, c->cfg.trace_capacity), max_records);
-  if (n > 0) HIPCHK(hipMemcpy(host_out, c->layers[layer].trace, (size_t)n * sizeof(moe_trace_rec_t), hipMemcpyDeviceToHost));
+  if (n > 0) HIPCHK(hipMemcpy(host_out, state_of(c, layer).trace, (size_t)n * sizeof(moe_trace_rec_t), hipMemcpyDeviceToHost));
   *n_out = n;
   if (n_total) *n_total = total;
   return MOE_OK;
@@ -870,7 +964,7 @@ int moe_cache_resident(moe_cache_t* c, int32_t layer, int32_t* host_out, int32_t
   HIPCHK(guard.enter(c->device));
   HIPCHK(hipDeviceSynchronize());
   std::vector<int32_t> ein(c->C);
-  HIPCHK(hipMemcpy(ein.data(), c->layers[layer].expert_in, (size_t)c->C * 4, hipMemcpyDeviceToHost));
+  HIPCHK(hipMemcpy(ein.data(), state_of(c, layer).expert_in, (size_t)c->C * 4, hipMemcpyDeviceToHost));
   std::vector<int32_t> res;
   for (int v : ein) if (v >= 0) res.push_back(v);
   std::sort(res.begin(), res.end());
@@ -892,6 +986,9 @@ int moe_cache_set_profiling(moe_cache_t* c, int32_t enabled) {
         HIPCHK(hipEventCreate(&ke->stop));
       }
     for (auto& p : c->cprof) { HIPCHK(hipEventCreate(&p.c0)); HIPCHK(hipEventCreate(&p.c1)); }
+    HIPCHK(hipHostMalloc(reinterpret_cast<void**>(&c->call_log), kProfSlots * sizeof(Mailbox),
+                         hipHostMallocMapped | hipHostMallocCoherent));
+    memset(c->call_log, 0, kProfSlots * sizeof(Mailbox));
   }
   c->profiling = enabled != 0;
   return MOE_OK;

@@ -104,6 +104,20 @@ struct RouteArgs {
   int32_t* arrive;        // [1] workgroup arrival counter, zero between launches
 };
 
+// Everything the single-launch decode kernel needs beyond FfnArgs: it routes and looks up itself.  Every
+// workgroup repeats the routing and the lookups from the table `st_in` (read-only during the launch) and reaches
+// the same result; one extra workgroup alone writes the table after the call to `st_out` (the layer's other
+// copy), the gate weights, the trace, the counters and the call record.  The host swaps the two copies after the
+// launch.
+struct RoutedArgs {
+  RouteArgs r;               // x, router_w, bias, d, norm_topk, user_idx, user_w (arrive unused)
+  const void* router_packed; // this layer's router matrix in matrix-core operand order (launch_pack_router)
+  LayerState st_in, st_out;
+  CacheCallArgs a;
+  unsigned long long* dev_stats;  // [3] hits, misses, evictions of the layer, accumulated on the device
+  Mailbox* log;              // optional second copy of the call record (host-mapped), for the profiler
+};
+
 // Pairs (token, expert) of a call are staged in LDS up to this many; larger calls use global scratch.
 constexpr size_t kStageMaxPairs = 2048;
 
@@ -117,7 +131,9 @@ size_t route_cache_lds_bytes(int E, int C, int P, int n_shared, int B, int K, in
 hipError_t launch_route_cache(hipStream_t s, int dtype, const RouteArgs& r, const LayerState& st, const CallTables& t,
                               const CacheCallArgs& a, KernelEvents ev);
 hipError_t launch_pin(hipStream_t s, const LayerState& st, const CallTables& t, const CacheCallArgs& a);
-hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace);
+// dev_stats: the layer's device-side counters (hits, misses, evictions), zeroed when non-null
+hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace,
+                        unsigned long long* dev_stats);
 hipError_t launch_ffn_rowmajor(hipStream_t s, int dtype, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 hipError_t launch_ffn_tiled(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
 hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);
@@ -131,6 +147,12 @@ constexpr int kFusedMaxTokens = 6;
 inline int fused_max_tokens(int d_ff) { return d_ff >= 4096 ? 8 : kFusedMaxTokens; }
 bool ffn_fused_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev);
+// Single-launch decode (router + gating + lookups + expert FFN; combine_chunks follows): shapes it covers, and
+// the launch.
+size_t router_packed_bytes(int E, int d);      // per layer
+hipError_t launch_pack_router(hipStream_t s, const void* router_w, void* out, int E, int d, int n_layers);
+bool decode_single_supported(int policy, int E, int C, int P, int n_shared, int K, int d, int f, int batch);
+hipError_t launch_decode_single(hipStream_t s, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev);
 bool ffn_fused_q4_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused_q4(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 hipError_t launch_ffn_gemm_q4(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);

@@ -26,20 +26,11 @@
 // Nothing is committed when the call runs out of spare buffers, so a failed call
 // leaves the cache unchanged.
 #include "device_utils.hpp"
+#include "gating.hpp"
 #include "moe_internal.hpp"
 
 namespace moe {
 
-#ifdef MOE_PHASE_TIMING
-// Development aid: 100 MHz timestamps of the phases of the last workgroup.
-__device__ long long g_phase_ts[16];
-#define PHASE_TS(i) do { if (threadIdx.x == 0) g_phase_ts[i] = wall_clock64(); } while (0)
-extern "C" int moe_debug_phase_ts(long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_ts), sizeof(long long) * 16);
-}
-#else
-#define PHASE_TS(i) do { } while (0)
-#endif
 
 namespace {
 
@@ -69,20 +60,6 @@ template <> struct Vec<uint16_t> {
   }
 };
 
-// ordering point between the lanes of ONE wave (LDS and global), no s_barrier
-__device__ __forceinline__ void wave_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
-  __builtin_amdgcn_wave_barrier();
-}
-
-__device__ __forceinline__ int readlane_i(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
-
-__device__ __forceinline__ int64_t uniform64(int64_t v) {
-  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
-  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uint64_t)v >> 32));
-  return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
 constexpr int kTileMaxE = 256;   // most experts the 16-token tile kernel keeps logits for
 
 // ---------------------------------------------------------------- LDS layout
@@ -92,11 +69,6 @@ struct LdsLayout {
 };
 
 __host__ __device__ inline bool stage_in_lds(int B, int KS) { return (size_t)B * KS <= kStageMaxPairs; }
-
-// The register-resident table: LRU, at most 64 slots and 64 buffers, and at most 128 buffer ids in all.
-__host__ __device__ inline bool fast_table(int policy, int C, int P, int n_shared) {
-  return policy == MOE_POLICY_LRU && C <= kWave && P <= kWave && P + n_shared <= 2 * kWave;
-}
 
 __host__ __device__ inline LdsLayout lds_layout(int E, int C, int P, int n_shared, int B, int K, int KS) {
   LdsLayout l;
@@ -120,95 +92,6 @@ __host__ __device__ inline LdsLayout lds_layout(int E, int C, int P, int n_share
   l.pair_stage = o; o += stage ? (size_t)B * KS * 4 : 0;
   l.total = o;
   return l;
-}
-
-// ---------------------------------------------------------------- phase 2
-// One wave gates one token from the logits in LDS (zs[E]).
-template <int EPL>
-__device__ __forceinline__ void gate_token(const float* zs, int b, int E, int K, int KS, int norm_topk,
-                                           int32_t* idx_g, float* wpair_g, int32_t* user_idx, float* user_w,
-                                           int32_t* idx_stage) {
-  const int lane = threadIdx.x & 63;
-  float z[EPL];
-  bool sel[EPL];
-  float zmax = -INFINITY;
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) {
-    const int e = lane + i * kWave;
-    z[i] = e < E ? zs[e] : -INFINITY;
-    sel[i] = false;
-    zmax = fmaxf(zmax, z[i]);
-  }
-  zmax = wave_max(zmax);
-  if (K <= 16) {
-    // K rounds of arg-max; a taken entry is masked out; ties resolve to the lowest id
-    float zc[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) zc[i] = z[i];
-    for (int k = 0; k < K; ++k) {
-      float m = zc[0];
-#pragma unroll
-      for (int i = 1; i < EPL; ++i) m = fmaxf(m, zc[i]);
-      m = wave_max(m);
-      bool done = false;
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        const uint64_t cand = __ballot(zc[i] == m && (lane + i * kWave) < E);
-        if (!done && cand != 0) {          // uniform
-          const int first = __ffsll((unsigned long long)cand) - 1;
-          if (lane == first) { sel[i] = true; zc[i] = -INFINITY; }
-          done = true;
-        }
-      }
-    }
-  } else {
-    // rank every logit against all others (ties to the lower id)
-    int rank[EPL];
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) rank[i] = 0;
-    for (int j = 0; j < E; ++j) {
-      const float zj = zs[j];  // same address in every lane: LDS broadcast
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        const int e = lane + i * kWave;
-        rank[i] += (zj > z[i] || (zj == z[i] && j < e)) ? 1 : 0;
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) sel[i] = (lane + i * kWave) < E && rank[i] < K;
-  }
-  float p[EPL];
-  float psum = 0.f;
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) {
-    p[i] = (lane + i * kWave) < E ? expf(z[i] - zmax) : 0.f;
-    psum += p[i];
-  }
-  psum = wave_sum(psum);
-  float selsum = 0.f;
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) {
-    p[i] = p[i] / psum;
-    selsum += sel[i] ? p[i] : 0.f;
-  }
-  selsum = wave_sum(selsum);
-  int base = 0;
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) {
-    const int e = lane + i * kWave;
-    const uint64_t m = __ballot(sel[i]);
-    if (sel[i]) {
-      const int pos = base + __popcll(m & ((1ull << lane) - 1ull));   // ascending expert id
-      const float w = norm_topk ? p[i] / selsum : p[i];
-      idx_g[(size_t)b * K + pos] = e;
-      wpair_g[(size_t)b * KS + pos] = w;
-      if (idx_stage) idx_stage[(size_t)b * K + pos] = e;
-      if (user_idx) user_idx[(size_t)b * K + pos] = e;
-      if (user_w) user_w[(size_t)b * K + pos] = w;
-    }
-    base += __popcll(m);
-  }
-  if (lane < KS - K) wpair_g[(size_t)b * KS + K + lane] = 1.0f;  // shared experts: weight 1
 }
 
 // ---------------------------------------------------------------- grouping (any number of pairs)
@@ -384,7 +267,6 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
   for (int s = lane; s < C; s += kWave)       // expert -> slot index, rebuilt from the slots
     if (expert_in[s] >= 0) slot_of[expert_in[s]] = s;
   wave_sync();
-  PHASE_TS(4);
 
   const uint32_t seq = a.seq;
   const int n_lookups = a.mode == 0 ? a.B * K : K;
@@ -480,14 +362,11 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
       wave_sync();
     }
   }
-
-  PHASE_TS(5);
   int n_groups = 0;
   if (status == MOE_OK && a.mode == 0) {
     n_groups = group_pairs_lds(count, start, filled, pair_buf, t, a);
   }
   if (a.mode == 0 && lane == 0) *t.n_groups = n_groups;
-  PHASE_TS(6);
 
   if (status == MOE_OK) {
     // ---- commit ----
@@ -509,7 +388,6 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
       st.scalars[SC_TRACE_N] = trace_n + trace_added;
     }
   }
-  PHASE_TS(7);
   if (lane == 0) {
     Mailbox* mb = a.mailbox;
     mb->status = status;
@@ -519,61 +397,6 @@ __device__ void cache_phase_general(unsigned char* smem, const LdsLayout& L, con
     mb->n_hits = n_hits;
     mb->seq = seq;   // read by the host only after the kernel has completed
   }
-  PHASE_TS(8);
-}
-
-// ---------------------------------------------------------------- phase 3, register path
-// LRU with at most 64 slots, 64 buffers and 64 (token, expert) pairs: lane s holds
-// slot s (expert, last-use tick, buffer), lane p holds buffer p's use stamp, lane i
-// holds entry i of the free and released-buffer stacks, lane q holds pair q.
-struct FastTable {
-  int exp, buf, free_b, zomb;
-  uint64_t tick;
-  uint32_t used;
-  int64_t clock, trace_n;
-  int n_res, n_free, n_zombie;
-};
-
-__device__ __forceinline__ FastTable fast_load(const LayerState& st, int C, int P) {
-  const int lane = threadIdx.x & 63;
-  FastTable f;
-  // the scalars are the same in every lane; telling the compiler so keeps the loops over them and the
-  // cross-lane reads indexed by them on the scalar unit
-  f.clock = uniform64(st.scalars[SC_CLOCK]);
-  f.n_res = __builtin_amdgcn_readfirstlane((int)st.scalars[SC_NRES]);
-  f.n_free = __builtin_amdgcn_readfirstlane((int)st.scalars[SC_NFREE]);
-  f.n_zombie = __builtin_amdgcn_readfirstlane((int)st.scalars[SC_NZOMBIE]);
-  f.trace_n = uniform64(st.scalars[SC_TRACE_N]);
-  f.exp = lane < C ? st.expert_in[lane] : -2;
-  f.tick = lane < C ? st.tick[lane] : ~0ull;
-  f.buf = lane < C ? st.buf_of_slot[lane] : -1;
-  f.used = lane < P ? st.used_stamp[lane] : 0u;
-  f.free_b = lane < P ? st.free_buf[lane] : -1;
-  f.zomb = lane < P ? st.zombie[lane] : -1;
-  return f;
-}
-
-// index of the lane (< C) holding the smallest tick; ticks of valid lanes are unique
-__device__ __forceinline__ int wave_argmin_tick(uint64_t tick) {
-  uint32_t hi = (uint32_t)(tick >> 32), lo = (uint32_t)tick;
-#define MOE_MIN_STEP(CTRL)                                                                              \
-  {                                                                                                     \
-    const uint32_t ohi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi, CTRL, 0xf, 0xf, true);       \
-    const uint32_t olo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, CTRL, 0xf, 0xf, true);       \
-    const bool less = ohi < hi || (ohi == hi && olo < lo);                                              \
-    hi = less ? ohi : hi;                                                                               \
-    lo = less ? olo : lo;                                                                               \
-  }
-  MOE_MIN_STEP(0xB1) MOE_MIN_STEP(0x4E) MOE_MIN_STEP(0x141) MOE_MIN_STEP(0x140)
-#undef MOE_MIN_STEP
-  uint64_t best = ~0ull;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const uint64_t v = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, r * 16) << 32) |
-                       (uint32_t)__builtin_amdgcn_readlane((int)lo, r * 16);
-    best = v < best ? v : best;
-  }
-  return __ffsll((unsigned long long)__ballot(tick == best)) - 1;
 }
 
 // Runs in ONE wave.  idx_src: the experts to look up, in order (decode: [B][K]; pin: the list);
@@ -605,7 +428,6 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
   int status = MOE_OK, n_miss = 0, n_evict = 0, n_hits = 0;
   int my_pair = -1;       // small calls: lane p = b*KS + k holds the buffer the pair reads
   int filled = 0;         // lane p: expert + 1 that this call brings into buffer p, 0 if none
-  PHASE_TS(4);
 
   // ---- shortcut for a call whose lookups all hit (the resident regime): residency does not change, and the
   //      recency updates commute - the last lookup of a slot decides its tick.  Lookups run 64 per step. ----
@@ -739,7 +561,6 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
       }
     }
   }
-  PHASE_TS(5);
 
   int n_groups = 0;
   if (status == MOE_OK && a.mode == 0) {
@@ -785,7 +606,6 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
     }
   }
   if (a.mode == 0 && lane == 0) *t.n_groups = n_groups;
-  PHASE_TS(6);
 
   if (status == MOE_OK) {
     // ---- commit ----
@@ -800,7 +620,6 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
       st.scalars[SC_TRACE_N] = f.trace_n + (a.mode == 0 ? n_lookups : 0);
     }
   }
-  PHASE_TS(7);
   if (lane == 0) {
     Mailbox* mb = a.mailbox;
     mb->status = status;
@@ -810,7 +629,6 @@ __device__ void cache_phase_fast(FastTable f, unsigned char* smem, const LdsLayo
     mb->n_hits = n_hits;
     mb->seq = seq;   // read by the host only after the kernel has completed
   }
-  PHASE_TS(8);
 }
 
 // ---------------------------------------------------------------- the decode launch
@@ -826,7 +644,6 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
   const int E = a.E, K = a.K, KS = a.KS, d = r.d;
   const bool single = gridDim.x == 1;
   const bool fast = a.mode != 2 && fast_table(a.policy, a.C, a.P, a.n_shared);
-  PHASE_TS(0);
 
   // With one workgroup the cache table can be fetched while the router GEMV runs.
   FastTable ft{};
@@ -882,24 +699,21 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
     }
   }
   __syncthreads();
-  PHASE_TS(1);
 
   // ---- phase 2: gating of token b by wave 0 ----
   if (wave != 0) return;
   if (E <= 64) gate_token<1>(zs, b, E, K, KS, r.norm_topk, t.idx, t.wpair, r.user_idx, r.user_w, idx_stage);
   else if (E <= 256) gate_token<4>(zs, b, E, K, KS, r.norm_topk, t.idx, t.wpair, r.user_idx, r.user_w, idx_stage);
   else gate_token<16>(zs, b, E, K, KS, r.norm_topk, t.idx, t.wpair, r.user_idx, r.user_w, idx_stage);
-  PHASE_TS(2);
 
   if (!single) {
     // ---- the last workgroup to arrive carries on (no waiting anywhere) ----
-    if (lane == 0) {
-      __threadfence();
-      s_last = atomicAdd(r.arrive, 1) == (int)gridDim.x - 1;
-    }
+    // every lane publishes its own stores (routing results) before lane 0 announces the workgroup
+    __threadfence();
+    if (lane == 0) s_last = atomicAdd(r.arrive, 1) == (int)gridDim.x - 1;
     wave_sync();
     if (!s_last) return;
-    if (lane == 0) *r.arrive = 0;   // ready for the next launch on this stream
+    if (lane == 0) __hip_atomic_store(r.arrive, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch on this stream
     __threadfence();
     // routing results of the other workgroups: read at device scope
     if (stage)
@@ -908,7 +722,6 @@ __global__ void __launch_bounds__(1024) route_cache_kernel(RouteArgs r, LayerSta
     if (fast) ft = fast_load(st, a.C, a.P);
   }
   wave_sync();
-  PHASE_TS(3);
 
   // ---- phase 3: cache lookups, one wave ----
   if (a.mode == 2) {
@@ -1108,7 +921,7 @@ __global__ void __launch_bounds__(1024) route_tile_kernel(RouteArgs r, LayerStat
   if (threadIdx.x == 0) s_last = atomicAdd(r.arrive, 1) == (int)gridDim.x - 1;
   __syncthreads();
   if (!s_last) return;
-  if (threadIdx.x == 0) *r.arrive = 0;   // ready for the next launch on this stream
+  if (threadIdx.x == 0) __hip_atomic_store(r.arrive, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch on this stream
   __threadfence();
   const LdsLayout L = lds_layout(E, a.C, a.P, a.n_shared, a.B, K, KS);
   const bool stage = stage_in_lds(a.B, KS);
@@ -1135,7 +948,7 @@ __global__ void __launch_bounds__(64) pin_kernel(LayerState st, CallTables t, Ca
   }
 }
 
-__global__ void reset_kernel(LayerState st, int E, int C, int P, int clear_trace) {
+__global__ void reset_kernel(LayerState st, int E, int C, int P, int clear_trace, unsigned long long* dev_stats) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < C) { st.expert_in[i] = -1; st.tick[i] = 0; st.buf_of_slot[i] = -1; }
   if (i < E) st.score[i] = 0.0;
@@ -1146,6 +959,7 @@ __global__ void reset_kernel(LayerState st, int E, int C, int P, int clear_trace
     st.scalars[SC_NFREE] = P;
     st.scalars[SC_NZOMBIE] = 0;
     if (clear_trace) st.scalars[SC_TRACE_N] = 0;
+    if (dev_stats) dev_stats[0] = dev_stats[1] = dev_stats[2] = 0;
   }
 }
 
@@ -1167,10 +981,8 @@ hipError_t launch_route_cache(hipStream_t s, int dtype, const RouteArgs& r, cons
   // phase on all waves of the last workgroup wins (measured: 31 against 48 us at 256 tokens, 49 against 182 us at 1024;
   // 28.6 against 26.6 at 96, 29.3 against 31.6 at 127)
   if (dtype == MOE_DTYPE_BF16 && a.B >= 112 && a.E <= kTileMaxE && r.d % 32 == 0) {
-#ifndef MOE_ROUTE_TILE_WAVES
-#define MOE_ROUTE_TILE_WAVES 8      // measured: 49 us at 1024 tokens against 61 with four waves and 54 with sixteen
-#endif
-    launch_timed(route_tile_kernel, dim3((a.B + 15) / 16), dim3(64 * MOE_ROUTE_TILE_WAVES), lds, s, ev, r, st, t, a);
+    constexpr int kTileWaves = 8;   // measured: 49 us at 1024 tokens against 61 with four waves and 54 with sixteen
+    launch_timed(route_tile_kernel, dim3((a.B + 15) / 16), dim3(64 * kTileWaves), lds, s, ev, r, st, t, a);
     return hipGetLastError();
   }
   const bool one_row = a.E <= waves;
@@ -1190,10 +1002,11 @@ hipError_t launch_pin(hipStream_t s, const LayerState& st, const CallTables& t, 
   return hipGetLastError();
 }
 
-hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace) {
+hipError_t launch_reset(hipStream_t s, const LayerState& st, int E, int C, int P, int clear_trace,
+                        unsigned long long* dev_stats) {
   int n = E > C ? E : C;
   n = n > P ? n : P;
-  hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, E, C, P, clear_trace);
+  hipLaunchKernelGGL(reset_kernel, dim3((n + 255) / 256), dim3(256), 0, s, st, E, C, P, clear_trace, dev_stats);
   return hipGetLastError();
 }
 

@@ -1,4 +1,4 @@
-"""Host-side checks of bench.py that need no GPU: the multi-GPU refusal and the workload the default line names."""
+"""Host-side checks of bench.py that need no GPU: the multi-GPU refusal and the workloads the default run covers."""
 import json
 import os
 import subprocess
@@ -14,7 +14,10 @@ def test_more_than_one_gpu_is_refused_with_a_message():
     assert "single-GPU" in r.stderr and r.stdout.strip() == ""
 
 
-def test_default_workload_is_the_one_the_baseline_metric_is_quoted_on():
+def test_default_run_covers_both_configurations_the_bandwidth_target_names():
+    """The baseline's metric names no configuration; its target sentence names the OLMoE-like and the Mixtral-like
+    ones.  The default line is quoted on the OLMoE-like layer (the second baseline configuration) and carries a
+    section for a cut of the Mixtral-like stack (the third)."""
     sys.path.insert(0, ROOT)
     import bench
     from workload import get_config
@@ -24,11 +27,11 @@ def test_default_workload_is_the_one_the_baseline_metric_is_quoted_on():
         a = bench.parse()
     finally:
         sys.argv = saved
-    assert a.gpus == 1 and a.workload == "olmoe_like"
+    assert a.gpus == 1 and a.workload == "olmoe_like" and a.second_layers > 0
     base = json.load(open(os.path.join(ROOT, "BASELINE.json")))
-    cfg = get_config(a.workload)
-    want = base["configs"][1]
-    text = json.dumps(want).lower()
-    # the second configuration of the baseline: OLMoE-like layer, 64 experts, top-8, capacity 16
-    for value in (cfg.n_experts, cfg.top_k, cfg.d_model, cfg.d_ff, cfg.capacity):
-        assert str(value) in text
+    assert "OLMoE-like and Mixtral-like" in base["north_star"]
+    for name, want in (("olmoe_like", base["configs"][1]), ("mixtral_like", base["configs"][2])):
+        cfg = get_config(name)
+        text = json.dumps(want).lower()
+        for value in (cfg.n_experts, cfg.top_k, cfg.d_model, cfg.d_ff, cfg.capacity, cfg.n_layers):
+            assert str(value) in text, (name, value)

@@ -40,9 +40,25 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+def _stale() -> bool:
+    """True if a source or header is newer than the built library."""
+    if not os.path.exists(LIB):
+        return True
+    built = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, n) for n in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "moe_cache.h")]
+    return any(os.path.getmtime(d) > built for d in deps if os.path.isfile(d))
+
+
 def ensure_built() -> str:
-    """Build only if no library is there (tests, smoke and the benchmark load what is built)."""
-    return LIB if os.path.exists(LIB) else build_library()
+    """Tests, smoke and the benchmark load what is built; build if nothing is there.  A library older than its
+    sources is rebuilt when a compiler is at hand, and refused otherwise: running stale kernels would test or
+    time something other than the sources say."""
+    if not _stale():
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if os.path.exists(LIB) and not os.path.exists(hipcc):
+        raise RuntimeError("libmoe_cache.so is older than its sources and no hipcc is available to rebuild it")
+    return build_library()
 
 
 if __name__ == "__main__":

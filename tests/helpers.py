@@ -55,11 +55,27 @@ def rel_err(y, ref):
     return np.abs(y - ref).max(axis=-1) / np.abs(ref).max(axis=-1)
 
 
-def run_sequence_serial(wl, cache, ostack, *, pins=True, y_every=1, seqs=None, steps=None, torch=None, pool=None):
+def elementwise_excess(y, ref, tol):
+    """Second error measure: largest |y_i - ref_i| / (tol |ref_i| + tol rms(ref)) over the elements of each token;
+    <= 1 means every element is within tol of its own magnitude plus the same share of the row's rms (a relative
+    error alone is unbounded near zeros)."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
+    return (np.abs(y - ref) / (tol * np.abs(ref) + tol * rms)).max(axis=-1)
+
+
+WORST_ELEMENTWISE = {"value": 0.0}      # largest elementwise_excess seen by run_sequence_serial (reported by tests)
+
+
+def run_sequence_serial(wl, cache, ostack, *, pins=True, y_every=1, seqs=None, steps=None, torch=None, pool=None,
+                        y_layers=None, y_seqs=None):
     """Schedule of the paper's main setting: one sequence at a time, batch 1;
     per sequence: empty the caches, preload the prefetch set, then T decode
     steps through all layers.  Returns the worst output error and checks
-    routing and traces on the way."""
+    routing and traces on the way.  Outputs are compared every y_every-th step
+    (of the layers / sequences in y_layers / y_seqs when given); routing, gate
+    weights and the cache trace are compared for every call."""
     from paper_2602_11192_amd import pool as P
     cfg = wl.cfg
     dev = "cuda:0"
@@ -86,8 +102,9 @@ def run_sequence_serial(wl, cache, ostack, *, pins=True, y_every=1, seqs=None, s
         biases = [wl.bias(l, s)[None, :] for l in range(cfg.n_layers)]
         biases_dev = [torch.from_numpy(b).to(dev) for b in biases]
         for t in range(steps):
-            want_y = (t % y_every) == 0
             for l in range(cfg.n_layers):
+                want_y = ((t % y_every) == 0 and (y_layers is None or l in y_layers) and
+                          (y_seqs is None or s in y_seqs))
                 cache.moe_layer_decode(l, x_dev[t:t + 1], y, biases_dev[l], idx, gw)
                 res = ostack.decode(l, x32[t:t + 1], biases[l], compute_y=want_y)
                 torch.cuda.synchronize()
@@ -97,6 +114,9 @@ def run_sequence_serial(wl, cache, ostack, *, pins=True, y_every=1, seqs=None, s
                 if want_y:
                     err = float(rel_err(P.to_numpy(y), res.y)[0])
                     assert err <= TOL[cfg.dtype], (s, t, l, err)
+                    ex = float(elementwise_excess(P.to_numpy(y), res.y, TOL[cfg.dtype])[0])
+                    assert ex <= 1.0, (s, t, l, ex)
+                    WORST_ELEMENTWISE["value"] = max(WORST_ELEMENTWISE["value"], ex)
                     worst = max(worst, err)
                     n_y += 1
     return worst, n_y, traces

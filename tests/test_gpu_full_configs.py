@@ -111,8 +111,6 @@ def test_olmoe_like_resident_path_batched(torch, P, olmoe, batch):
 @pytest.mark.parametrize("fetch", ["copy_engine", "in_kernel"])
 @pytest.mark.parametrize("name", ["mixtral_like", "phi35_like_concentrated", "phi35_like_diverse", "deepseek_like"])
 def test_one_layer_of_the_large_stacks(torch, P, name, fetch):
-    if fetch == "in_kernel" and name == "phi35_like_diverse":
-        pytest.skip("same kernels as phi35_like_concentrated")
     cfg = get_config(name).with_(n_layers=1, n_seqs=2, n_steps=24)
     wl = Workload(cfg)
     mode = P.B.MOE_FETCH_IN_KERNEL if fetch == "in_kernel" else P.B.MOE_FETCH_COPY_ENGINE

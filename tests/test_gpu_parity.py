@@ -288,6 +288,28 @@ def test_shared_cache_with_pooled_prefetch(torch, P):
     cache.close()
 
 
+@pytest.mark.parametrize("gamma", [0.3, 0.49])
+def test_gamma_policy_below_one_half_gives_the_lru_trace(torch, P, gamma):
+    """Remark after Definition C.1 on the device: one expert per token, gamma < 1/2 - the discounted-count policy
+    and LRU must produce the same trace, which is also the oracle's LRU trace."""
+    from paper_2602_11192_amd import binding as B
+    cfg = small_cfg(top_k=1, n_experts=12, capacity=5, n_layers=1, n_seqs=2, n_steps=150, pref_lo=0, pref_hi=0,
+                    beta=0.0, cfg_id=17)
+    wl = Workload(cfg)
+    traces = {}
+    for name, kw in (("gamma", dict(policy=B.MOE_POLICY_GAMMA, gamma=gamma)), ("lru", {})):
+        cache = P.make_cache(wl, tiled=True, trace_capacity=4096, **kw)
+        ost = OracleStack(wl)                       # the oracle runs LRU in both cases
+        _, _, tr = run_sequence_serial(wl, cache, ost, torch=torch, pins=False, y_every=50)
+        got, total = cache.moe_cache_read_trace(0)
+        assert total == len(tr[0]) and got.tolist() == [list(r) for r in tr[0]]
+        assert cache.moe_cache_resident(0) == ost.caches[0].resident()
+        traces[name] = got.tolist()
+        assert cache.moe_cache_stats(0)["evictions"] > 50
+        cache.close()
+    assert traces["gamma"] == traces["lru"]
+
+
 @pytest.mark.parametrize("gamma", [1.0, 0.9])
 def test_small_bf16_gamma_policy(torch, P, gamma):
     from paper_2602_11192_amd import binding as B

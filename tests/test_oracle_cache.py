@@ -207,6 +207,20 @@ def test_gamma_policy_matches_reference(gamma):
         assert trace == lfu_reference(reqs, E, C, gamma)
 
 
+@pytest.mark.parametrize("gamma", [0.3, 0.49])
+def test_gamma_policy_below_one_half_is_lru_for_one_expert_per_token(gamma):
+    """Remark after Definition C.1: for gamma < 1/2 the order of the discounted counts is the order of the last
+    uses (the most recent request outweighs all earlier ones together), so with one expert per token the gamma
+    policy must produce the LRU trace - against the move-to-front list, which shares nothing with the oracle."""
+    E, C = 12, 5
+    for reqs in (zipf_requests(31, E, 1, 400, a=0.6), random_requests(32, E, 1, 400)):
+        _, trace, residents = run_oracle(reqs, E, C, oracle.POLICY_GAMMA, gamma)
+        want, final = lru_move_to_front(reqs, C)
+        assert trace == want
+        assert residents[-1] == final
+        assert sum(1 for r in trace if r[3] >= 0) > 50          # the case does evict
+
+
 def test_lfu_keeps_the_frequent_expert():
     # expert 0 is requested every other token; under LFU it is never evicted once counted
     reqs = [[0] if t % 2 == 0 else [1 + (t // 2) % 6] for t in range(60)]

@@ -325,7 +325,7 @@ def int4_section(torch, P, wl, a):
     timed(torch, run.pass_sequence_serial, a.steps)
     tm = cache.moe_cache_timing(clear=True)
     cache.close()
-    rcache = P.make_cache(wl, int4=True, pool=pool, capacity=cfg.n_experts)
+    rcache = P.make_cache(wl, int4=True, pool=pool, capacity=cfg.n_experts, fetch_mode=P.B.MOE_FETCH_IN_KERNEL)
     rrun = Runner(wl, rcache, torch, P)
     for l in range(cfg.n_layers):
         rcache.moe_cache_prefill_pins(l, list(range(cfg.n_experts)))
@@ -351,8 +351,10 @@ def int4_section(torch, P, wl, a):
     n_pp, dt_pp = timed(torch, prompt_pass, 3)
     pst = pcache.moe_cache_stats()
     pcache.close()
-    k_bytes = (K + cfg.n_shared) * qb + d * 2 + (K + cfg.n_shared) * d * 4
-    k_ms = tm["ffn_fused_ms"] / max(1, tm["ffn_fused_launches"])
+    single = tm["decode_single_launches"] > 0
+    k_bytes = (K + cfg.n_shared) * qb + d * 2 + (K + cfg.n_shared) * d * 4 + (cfg.n_experts * d * 2 + cfg.n_experts * 4 if single else 0)
+    k_ms = (tm["decode_single_ms"] / tm["decode_single_launches"] if single
+            else tm["ffn_fused_ms"] / max(1, tm["ffn_fused_launches"]))
     return {"prompt_streaming": {"prompt_tokens": n_p, "ms_per_layer": dt_pp / 3 / cfg.n_layers * 1e3,
                                  "tokens_per_s": n_pp / dt_pp,
                                  "pcie_GBps_lower_bound": (pst["bytes_streamed"] - pst0["bytes_streamed"]) / dt_pp / 1e9},
@@ -360,11 +362,14 @@ def int4_section(torch, P, wl, a):
             "expert_bytes": qb, "tokens_per_s": n_tok / dt,
             "cache_hit_rate": st["hits"] / max(1, st["lookups"]), "misses_per_token": st["misses"] / max(1, n_tok),
             "pcie_GBps": tm["fetch_bytes"] / (tm["fetch_ms"] * 1e-3) / 1e9 if tm["fetch_ms"] > 0 else None,
-            "expert_kernel": {"bytes_per_launch": k_bytes, "avg_launch_ms": k_ms,
-                              "launches_timed": tm["ffn_fused_launches"],
+            "main_kernel": {"kernel": ("decode_single_q4_kernel (router, gating, lookups and the 4-bit expert FFN in one "
+                                       "launch)" if single else "ffn_fused_q4_kernel"),
+                            "bytes_per_launch": k_bytes, "avg_launch_ms": k_ms,
+                              "launches_timed": tm["decode_single_launches"] if single else tm["ffn_fused_launches"],
                               "achieved_GBps": k_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else None,
                               "frac_of_hbm_peak": k_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS if k_ms > 0 else None},
             "resident_path_tokens_per_s": n_r / dt_r,
+            "resident_path_us_per_layer_call": dt_r / n_r / cfg.n_layers * 1e6,
             "note": "same capacity C in experts (a quarter of the bytes); in-kernel fetch; outputs differ from the "
                     "bf16 run by the quantisation error, parity is against the oracle on the same 4-bit values"}
 

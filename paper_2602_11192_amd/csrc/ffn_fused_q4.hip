@@ -27,6 +27,7 @@
 #include "device_utils.hpp"
 #include "moe_internal.hpp"
 #include "q4_layout.hpp"
+#include "routed_prologue.hpp"
 
 namespace moe {
 
@@ -41,14 +42,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 // already take ~100 registers, and staying under 128 lets two workgroups share a compute unit, which hides the
 // start-up and the LDS reduction of one behind the streaming of the other (measured: 64 -> 47 us on the
 // Mixtral-like shape against rings of 4 and 8).
-#ifndef MOE_Q4_DEPTH_A
-#define MOE_Q4_DEPTH_A 1
-#endif
-#ifndef MOE_Q4_DEPTH_B
-#define MOE_Q4_DEPTH_B 4
-#endif
-constexpr int kDepthA = MOE_Q4_DEPTH_A;   // gate/up items (2.25 KiB each)
-constexpr int kDepthB = MOE_Q4_DEPTH_B;   // W_d items (1.125 KiB each)
+constexpr int kDepthA = 1;   // gate/up items (2.25 KiB each)
+constexpr int kDepthB = 4;   // W_d items (1.125 KiB each)
 
 template <typename V>
 __device__ __forceinline__ V ldnt(const void* p) {
@@ -79,14 +74,25 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
 
 // ONE: every group holds a single token (batch 1).  Only component 0 of the MFMA results (token 0 of the tile) is
 // then scaled and accumulated, which removes a quarter of the vector arithmetic that bounds this kernel.
-template <int WAVES, bool ONE>
-__global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
+// ROUTED: the launch is the decode call up to the combine; every workgroup first derives the routing, the cache
+// lookups and the groups for itself (routed_prologue.hpp).
+template <int WAVES, bool ONE, bool ROUTED>
+__device__ __forceinline__ void fused_q4_body(const FfnArgs& a, const RoutedArgs* rap) {
   __shared__ float red[WAVES][2][256];            // partial gate / up tiles of the waves
   __shared__ __align__(16) uint16_t hs[16][32];   // h of the chunk, bf16, [token][row in chunk]
-  const int g = blockIdx.y;
-  const int ng = *a.t.n_groups;
-  const GroupDesc gd = a.t.grp[g];
-  if (g >= ng || (a.pass != 2 && gd.miss != a.pass)) return;
+  __shared__ typename std::conditional<ROUTED, RoutedLds, int>::type rl_store;
+  GroupView gd;
+  int pair0 = 0;
+  if constexpr (ROUTED) {
+    if (!routed_prologue<WAVES>(a, *rap, rl_store, &red[0][0][0], gd)) return;
+  } else {
+    const int g = blockIdx.y;
+    const int ng = *a.t.n_groups;
+    const GroupDesc gdg = a.t.grp[g];
+    if (g >= ng || (a.pass != 2 && gdg.miss != a.pass)) return;
+    gd.buf = gdg.buf; gd.begin = gdg.begin; gd.count = gdg.count; gd.miss = gdg.miss; gd.expert = gdg.expert;
+    pair0 = gdg.pair0;
+  }
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -116,7 +122,9 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
   const int begin = gd.begin, cnt = gd.count;
   const uint16_t* xrow = nullptr;
   if (n < cnt) {
-    const int p = n == 0 ? gd.pair0 : a.t.sorted_pair[begin + n];
+    int p;
+    if constexpr (ROUTED) p = rl_store.sorted_pair[begin + n];
+    else p = n == 0 ? pair0 : a.t.sorted_pair[begin + n];
     xrow = reinterpret_cast<const uint16_t*>(a.x) + (size_t)(p / a.KS) * d + (size_t)ks * 128 + q * 8;
   }
 
@@ -232,17 +240,40 @@ __global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
   }
 }
 
-int pick_waves_q4(int d) {
-#ifdef MOE_Q4_FORCE_WAVES
-  if (d % (64 * MOE_Q4_FORCE_WAVES) == 0) return MOE_Q4_FORCE_WAVES;
-#endif
-  return d % 512 == 0 ? 8 : d % 256 == 0 ? 4 : 0;
+template <int WAVES, bool ONE>
+__global__ void __launch_bounds__(64 * WAVES) ffn_fused_q4_kernel(FfnArgs a) {
+  fused_q4_body<WAVES, ONE, false>(a, nullptr);
 }
+
+template <int WAVES, bool ONE>
+__global__ void __launch_bounds__(64 * WAVES, 4) decode_single_q4_kernel(FfnArgs a, RoutedArgs ra) {
+  fused_q4_body<WAVES, ONE, true>(a, &ra);
+}
+
+int pick_waves_q4(int d) { return d % 512 == 0 ? 8 : d % 256 == 0 ? 4 : 0; }
 
 }  // namespace
 
 bool ffn_fused_q4_supported(int d, int f, int max_count) {
   return max_count <= 16 && f % 32 == 0 && d >= 256 && pick_waves_q4(d) != 0;
+}
+
+int fused_q4_waves(int d) { return pick_waves_q4(d); }
+
+hipError_t launch_decode_single_q4(hipStream_t s, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev) {
+  dim3 grid(a.f / 32, a.g_max + 1);     // + the bookkeeping row
+  switch (pick_waves_q4(a.d)) {
+    case 8:
+      if (a.max_count == 1) launch_timed(decode_single_q4_kernel<8, true>, grid, dim3(512), 0, s, ev, a, ra);
+      else launch_timed(decode_single_q4_kernel<8, false>, grid, dim3(512), 0, s, ev, a, ra);
+      break;
+    case 4:
+      if (a.max_count == 1) launch_timed(decode_single_q4_kernel<4, true>, grid, dim3(256), 0, s, ev, a, ra);
+      else launch_timed(decode_single_q4_kernel<4, false>, grid, dim3(256), 0, s, ev, a, ra);
+      break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_ffn_fused_q4(hipStream_t s, const FfnArgs& a, KernelEvents ev) {

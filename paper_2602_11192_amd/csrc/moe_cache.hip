@@ -591,9 +591,12 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
       }
     }
   }
-  if (cfg->pool_layout == MOE_LAYOUT_TILED && cfg->fetch_mode == MOE_FETCH_IN_KERNEL && !c->pool_dev.empty()) {
-    for (int b = 1; b <= std::min(Bm, fused_max_tokens(cfg->d_ff)); ++b)
-      if (decode_single_supported(cfg->policy, E, C, P, cfg->n_shared, K, cfg->d_model, cfg->d_ff, b)) c->single_max_batch = b;
+  if ((cfg->pool_layout == MOE_LAYOUT_TILED || cfg->pool_layout == MOE_LAYOUT_TILED_INT4) &&
+      cfg->fetch_mode == MOE_FETCH_IN_KERNEL && !c->pool_dev.empty()) {
+    const int b_max = cfg->pool_layout == MOE_LAYOUT_TILED ? fused_max_tokens(cfg->d_ff) : 16;
+    for (int b = 1; b <= std::min(Bm, b_max); ++b)
+      if (decode_single_supported(cfg->pool_layout, cfg->policy, E, C, P, cfg->n_shared, K, cfg->d_model, cfg->d_ff, b))
+        c->single_max_batch = b;
       else break;
     c->single_ok = c->single_max_batch >= 1;
   }
@@ -733,7 +736,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
     fa.fused = 1; fa.pass = 2;
     fa.pool = c->pool_dev[layer];
     fa.fetch = 1;
-    HIPCHK(launch_decode_single(s, fa, q, ps ? ps->gate_up : KernelEvents{}));
+    HIPCHK(launch_decode_single(s, cf.pool_layout, fa, q, ps ? ps->gate_up : KernelEvents{}));
     HIPCHK(launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev));
     c->cur[layer] ^= 1;
     c->dev_stats_used = true;

@@ -151,8 +151,11 @@ hipError_t launch_ffn_fused(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 // the launch.
 size_t router_packed_bytes(int E, int d);      // per layer
 hipError_t launch_pack_router(hipStream_t s, const void* router_w, void* out, int E, int d, int n_layers);
-bool decode_single_supported(int policy, int E, int C, int P, int n_shared, int K, int d, int f, int batch);
-hipError_t launch_decode_single(hipStream_t s, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev);
+bool decode_single_supported(int pool_layout, int policy, int E, int C, int P, int n_shared, int K, int d, int f,
+                             int batch);
+hipError_t launch_decode_single(hipStream_t s, int pool_layout, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev);
+hipError_t launch_decode_single_q4(hipStream_t s, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev);
+int fused_q4_waves(int d);
 bool ffn_fused_q4_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused_q4(hipStream_t s, const FfnArgs& a, KernelEvents ev);
 hipError_t launch_ffn_gemm_q4(hipStream_t s, const FfnArgs& a, KernelEvents gate_up, KernelEvents down);

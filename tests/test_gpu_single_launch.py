@@ -124,3 +124,22 @@ def test_mixing_single_launch_calls_with_the_other_paths(torch, P):
         traces[0].extend(batched_step(torch, P, wl, cache, ost, 0, rows, step))
     compare_traces_and_stats(cache, ost, traces, cfg.expert_bytes)
     cache.close()
+
+
+@pytest.mark.parametrize("E,K,cap,ns,d,f", [(16, 4, 6, 0, 256, 96), (64, 8, 16, 0, 512, 64), (24, 3, 7, 2, 256, 128)])
+def test_int4_batch1_constrained_cache(torch, P, E, K, cap, ns, d, f):
+    """The same single launch on 4-bit experts (values compared with the oracle's own dequantisation)."""
+    B = P.B
+    cfg = small_cfg(n_experts=E, top_k=K, capacity=cap, n_shared=ns, d_model=d, d_ff=f, n_layers=2, n_seqs=3,
+                    n_steps=16, pref_lo=min(K, 4), pref_hi=min(K + 1, E), beta=1.5, cfg_id=45)
+    wl = Workload(cfg)
+    cache = P.make_cache(wl, int4=True, trace_capacity=8192, fetch_mode=B.MOE_FETCH_IN_KERNEL)
+    ost = OracleStack(wl, keep=min(E, 24), int4=True)
+    _, _, traces = run_sequence_serial(wl, cache, ost, torch=torch, pins=True)
+    compare_traces_and_stats(cache, ost, traces, P.int4_block_bytes(cfg))
+    assert cache.moe_cache_stats()["misses"] > 0
+    x = P.to_device(wl.tokens(0)[:1])
+    y = torch.empty((1, d), dtype=torch.bfloat16, device="cuda:0")
+    tm = timing_counts(cache, lambda: [cache.moe_layer_decode(0, x, y) for _ in range(4)])
+    assert tm["decode_single_launches"] + tm["fetch_launches"] == 4 and tm["route_launches"] == 0
+    cache.close()

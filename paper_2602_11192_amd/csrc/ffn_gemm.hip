@@ -48,6 +48,9 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
 // kTokTile: tokens per workgroup (64, 128 or 256).  128 shares every weight fragment among more tokens; 64 needs half the
 // accumulators and LDS, so more workgroups run side by side and hide each other's load latency: faster while an
 // expert sees at most ~64 tokens (measured 169 against 212 us at 32 tokens per expert).
+// (Holding more stages of weights in registers - three stages in flight instead of one - and fetching the tokens
+// two stages ahead were both measured on the eight-wave variants at 128-1024 tokens per call: within +-3 %, and
+// slower at 256; the one-stage look-ahead below stays.)
 // kGemmWaves: row tiles (waves) per workgroup.  Eight waves share one staged token tile among 128 output rows,
 // which halves the staging work per weight byte: faster once experts see ~128 tokens (302 against 335 us at 1024
 // tokens per call, 488 against 576 us at 2048); four waves leave more workgroups per compute unit and are better
@@ -211,25 +214,19 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, Ker
   // the group sizes are not known on the host; the mean load decides the token tile
   // (experts streamed from the host are read once per token tile: the large tile keeps that to one read up to 128 tokens)
   const int64_t load = (int64_t)a.max_count * a.KS;     // (token, expert) pairs of the call, all groups together
-#ifndef MOE_GEMM_SMALL_MAX
-#define MOE_GEMM_SMALL_MAX 24
-#endif
+  constexpr int kSmallMax = 24;
   // (mean pairs per group; measured on the OLMoE-like layer: the 64-token tile on four waves is level with the
   // 128-token tile on eight waves up to ~24 and loses beyond - 165 against 147 us at 32, 243 against 205 us at 64 -
   // because the busier experts then need a second tile)
-  const bool small_tile = a.fetch == 0 && load <= (int64_t)MOE_GEMM_SMALL_MAX * a.g_max;
+  const bool small_tile = a.fetch == 0 && load <= (int64_t)kSmallMax * a.g_max;
   // 256-token tiles: an expert with 129-256 tokens then streams its weights once instead of twice.  The gate/up
   // pass (both accumulator sets on the wave: 204 registers, one workgroup per compute unit) gains from a mean of ~52
   // pairs per expert on (118 against 126 us at 56, 164 against 184 us at 128; 113 against 103 us at 48); the down pass, which runs two workgroups per unit
   // with the 128-token tile, only from ~200 (180 against 188 us at 2048, but 126 against 109 us at 1024).
-#ifndef MOE_GEMM_BIG_UP
-#define MOE_GEMM_BIG_UP 52
-#endif
-  const bool big_up = a.fetch == 0 && load > (int64_t)MOE_GEMM_BIG_UP * a.g_max;
-#ifndef MOE_GEMM_BIG_DOWN
-#define MOE_GEMM_BIG_DOWN 192
-#endif
-  const bool big_down = a.fetch == 0 && load > (int64_t)MOE_GEMM_BIG_DOWN * a.g_max;
+  constexpr int kBigUp = 52;
+  const bool big_up = a.fetch == 0 && load > (int64_t)kBigUp * a.g_max;
+  constexpr int kBigDown = 192;
+  const bool big_down = a.fetch == 0 && load > (int64_t)kBigDown * a.g_max;
   const int waves = (small_tile || a.fetch != 0) ? 4 : 8;
   auto grid = [&](int rows, int tok_tile, int wv) {
     return dim3((rows / 16 + wv - 1) / wv, a.g_max, (a.max_count + tok_tile - 1) / tok_tile);
@@ -241,13 +238,10 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, Ker
   else if (big_up) launch_timed(ffn_gemm_kernel<2, 256, 8>, grid(a.f, 256, 8), b8, 0, s, e1, a);
   else launch_timed(ffn_gemm_kernel<2, 128, 8>, grid(a.f, 128, 8), b8, 0, s, e1, a);
   // ---- down ----
-#ifndef MOE_GEMM_DEEP_DOWN
-#define MOE_GEMM_DEEP_DOWN 1
-#endif
   // A long contraction with few output rows (Mixtral-like: d_ff = 14336, 8 experts) leaves the down pass with one
   // or two workgroups per compute unit, each waiting for one KiB per wave and step: four k-blocks per step and the
   // 64-row workgroups (measured on that layer: 205 against 314 us at 8 tokens per call).
-  const bool deep_down = MOE_GEMM_DEEP_DOWN && small_tile && a.f >= 4096 &&
+  const bool deep_down = small_tile && a.f >= 4096 &&
                          (int64_t)((a.d / 16 + 3) / 4) * a.g_max < 4 * 256;
   if (deep_down) launch_timed(ffn_gemm_kernel<1, 64, 4, 4>, grid(a.d, 64, 4), b4, 0, s, e2, a);
   else if (small_tile) launch_timed(ffn_gemm_kernel<1, 64, 4>, grid(a.d, 64, 4), b4, 0, s, e2, a);

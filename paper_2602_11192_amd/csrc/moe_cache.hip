@@ -737,7 +737,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
     fa.pool = c->pool_dev[layer];
     fa.fetch = 1;
     HIPCHK(launch_decode_single(s, cf.pool_layout, fa, q, ps ? ps->gate_up : KernelEvents{}));
-    HIPCHK(launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev));
+    HIPCHK(launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev, batch == 1));
     c->cur[layer] ^= 1;
     c->dev_stats_used = true;
     c->stats[layer].lookups += (uint64_t)batch * K;

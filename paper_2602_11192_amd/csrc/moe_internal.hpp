@@ -163,8 +163,9 @@ hipError_t launch_ffn_gemm_q4(hipStream_t s, const FfnArgs& a, KernelEvents gate
 struct FfnPlan { bool fused, gemm, tiled, q4; };
 FfnPlan plan_ffn(int pool_layout, int d, int f, int batch);
 hipError_t launch_ffn(hipStream_t s, int dtype, const FfnPlan& p, const FfnArgs& a, KernelEvents ke1, KernelEvents ke2);
+// identity: pair (b, j) has partial row b * KS + j (pos_of is not read)
 hipError_t launch_combine_chunks(hipStream_t s, const float* o_part, const float* wpair, const int32_t* pos_of,
-                                 int B, int KS, int d, int n_chunks, void* y);
+                                 int B, int KS, int d, int n_chunks, void* y, bool identity = false);
 hipError_t launch_combine(hipStream_t s, int dtype, const float* o, const float* wpair, const int32_t* pos_of,
                           int B, int KS, int d, void* y);
 

@@ -80,7 +80,9 @@ __device__ __forceinline__ void fused_body(const FfnArgs& a, const RoutedArgs* r
   __shared__ typename std::conditional<ROUTED, RoutedLds, int>::type rl_store;
   const int g = blockIdx.y;
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  // (the wave index is the same in all lanes of a wave: saying so keeps everything derived from it - row tile,
+  // contraction slice, fragment offsets - in scalar registers)
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int c = blockIdx.x;  // chunk of 32 intermediate rows
 
   int gd_buf, gd_begin, gd_count, gd_miss, gd_expert, gd_pair0;

@@ -95,7 +95,7 @@ __device__ __forceinline__ void fused_q4_body(const FfnArgs& a, const RoutedArgs
   }
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: the same in all lanes of a wave
   const int n = lane & 15;   // A operand: token row; B operand and D: weight row (column of D)
   const int q = lane >> 4;   // operands: 8-wide slice of the k-block; D: tokens 4q .. 4q+3
   const int c = blockIdx.x;  // chunk of 32 intermediate rows

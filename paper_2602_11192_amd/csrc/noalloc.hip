@@ -95,31 +95,44 @@ extern "C" int moe_layer_decode_resident_noalloc(const moe_resident_layer_t* L, 
   const size_t NP = (size_t)batch * KS;
   const int G = (int)std::min<size_t>((size_t)batch * K, (size_t)E) + ns;
   const size_t max_miss = std::max<size_t>((size_t)batch * K, (size_t)E);
-  const FfnPlan plan = plan_ffn(L->pool_layout, d, f, batch);
+  FfnPlan plan = plan_ffn(L->pool_layout, d, f, batch);
 
   // ---- carve the array ----
-  size_t o = 0;
-  const size_t o_tick = o; o += up((size_t)E * 8);
-  const size_t o_score = o; o += up((size_t)E * 8);
-  const size_t o_scal = o; o += up((size_t)SC_COUNT * 8);
-  const size_t o_ein = o; o += up((size_t)E * 4);
-  const size_t o_bos = o; o += up((size_t)E * 4);
-  const size_t o_free = o; o += up((size_t)E * 4);
-  const size_t o_zom = o; o += up((size_t)E * 4);
-  const size_t o_used = o; o += up((size_t)E * 4);
-  const size_t o_idx = o; o += up((size_t)batch * K * 4);
-  const size_t o_wp = o; o += up(NP * 4);
-  const size_t o_pb = o; o += up(NP * 4);
-  const size_t o_sp = o; o += up(NP * 4);
-  const size_t o_po = o; o += up(NP * 4);
-  const size_t o_gd = o; o += up((size_t)G * sizeof(GroupDesc));
-  const size_t o_ng = o; o += 256;
-  const size_t o_arr = o; o += 256;
-  const size_t o_mail = o; o += up(sizeof(Mailbox));
-  const size_t o_miss = o; o += up(max_miss * sizeof(MissEntry));
-  const size_t o_h = o; o += plan.fused ? 0 : up(NP * (size_t)f * 4);
-  const size_t o_o = o;
-  o += up(plan.fused ? NP * (size_t)(f / 32) * d * 4 : NP * (size_t)d * 4);
+  size_t o_tick, o_score, o_scal, o_ein, o_bos, o_free, o_zom, o_used, o_idx, o_wp, o_pb, o_sp, o_po, o_gd, o_ng,
+      o_arr, o_mail, o_miss, o_h, o_o;
+  auto carve = [&]() {
+    size_t o = 0;
+    o_tick = o; o += up((size_t)E * 8);
+    o_score = o; o += up((size_t)E * 8);
+    o_scal = o; o += up((size_t)SC_COUNT * 8);
+    o_ein = o; o += up((size_t)E * 4);
+    o_bos = o; o += up((size_t)E * 4);
+    o_free = o; o += up((size_t)E * 4);
+    o_zom = o; o += up((size_t)E * 4);
+    o_used = o; o += up((size_t)E * 4);
+    o_idx = o; o += up((size_t)batch * K * 4);
+    o_wp = o; o += up(NP * 4);
+    o_pb = o; o += up(NP * 4);
+    o_sp = o; o += up(NP * 4);
+    o_po = o; o += up(NP * 4);
+    o_gd = o; o += up((size_t)G * sizeof(GroupDesc));
+    o_ng = o; o += 256;
+    o_arr = o; o += 256;
+    o_mail = o; o += up(sizeof(Mailbox));
+    o_miss = o; o += up(max_miss * sizeof(MissEntry));
+    o_h = o; o += plan.fused ? 0 : up(NP * (size_t)f * 4);
+    o_o = o;
+    o += up(plan.fused ? NP * (size_t)(f / 32) * d * 4 : NP * (size_t)d * 4);
+    return o;
+  };
+  size_t o = carve();
+  if (o > kScratchBytes && plan.fused) {
+    // the single-launch kernels keep one partial row per 32 rows of d_ff; when those do not fit, the two-pass
+    // grouped GEMM (one row per pair) does the same work in a fraction of the scratch
+    plan.fused = false;
+    plan.gemm = plan.tiled;
+    o = carve();
+  }
   if (o > kScratchBytes)
     return fail(MOE_ERR_UNSUPPORTED,
                 "batch %d of this layer shape needs %zu bytes of scratch; the allocation-free entry point has %zu",

@@ -214,7 +214,7 @@ __device__ inline void lookup_small(FastTable f, RoutedLds& rl, const RoutedArgs
 // floats).
 template <int WAVES>
 __device__ __forceinline__ void route_logits(const RoutedArgs& ra, float* pz, RoutedLds& rl) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, q = lane >> 4;
   const int B = ra.a.B, E = ra.a.E, d = ra.r.d;
   const int nkb = d >> 5;
@@ -305,7 +305,7 @@ struct GroupView { int buf, begin, count, miss, expert; };
 template <int WAVES>
 __device__ __forceinline__ bool routed_prologue(const FfnArgs& a, const RoutedArgs& ra, RoutedLds& rl, float* pz,
                                                 GroupView& gd) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int g = blockIdx.y;
   const bool keeper = g == a.g_max;
   if (keeper && blockIdx.x != 0) return false;

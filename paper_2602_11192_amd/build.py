@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_cache.so")
 SOURCES = ["moe_cache.hip", "route_cache.hip", "ffn_rowmajor.hip", "ffn_tiled.hip", "ffn_fused.hip", "ffn_gemm.hip", "stream_probe.hip",
-           "cache_sim.hip", "ffn_fused_q4.hip", "ffn_gemm_q4.hip", "noalloc.hip"]
+           "cache_sim.hip", "ffn_fused_q4.hip", "ffn_gemm_q4.hip", "noalloc.hip", "ffn_tiles.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -1,0 +1,220 @@
+// Single-token decode call (paper section 2: router, Top-K, expert-cache lookups, SwiGLU experts of Eq. 3) on
+// layers whose experts are too large for one workgroup per 32 intermediate rows to fit the GPU at once.
+//
+// The chunk kernel (ffn_fused.hip) launches d_ff / 32 workgroups per expert.  On a Mixtral-like layer that is
+// 3.5 workgroups per compute unit: every one of them repeats the routing prologue, the last half round leaves
+// compute units idle, and the combine reads 448 partial rows per expert.  Here the launch has ONE workgroup
+// per compute unit: the 16-row tiles of an expert's intermediate dimension are dealt evenly (counts differ by
+// at most one tile) to n_parts workgroups, n_parts * groups <= compute units.  A workgroup of eight waves
+//   phase A: for each of its tiles, h[16 rows] = silu(W_g x) * (W_u x); the waves split the contraction
+//            (k-block kb belongs to wave kb % 8), the partial tiles meet in LDS once, after the last tile;
+//   phase B: o_part[d] = W_d[:, its rows] h: row tile rt of W_d belongs to wave rt % 8 and is accumulated over
+//            the workgroup's k-blocks in one register tile; a k-block that straddles two workgroups is read half
+//            by each (the lanes of the other half load nothing and multiply zeros);
+// and writes ONE partial row per (expert, workgroup): the combine reads n_parts rows per expert.
+// As in the chunk kernel every wave runs one software-pipelined stream over all its fragments, D in flight, the
+// first W_d loads under way while h is reduced.  The launch is the whole call up to the combine: every workgroup
+// runs the routing prologue of routed_prologue.hpp first, one more row of the grid holds the bookkeeping workgroup.
+#include <algorithm>
+
+#include "device_utils.hpp"
+#include "moe_internal.hpp"
+#include "routed_prologue.hpp"
+
+namespace moe {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTilesWaves = 8;
+constexpr int kTilesMaxT = 16;      // tiles per workgroup the LDS scratch holds
+constexpr int kXv = (kRoutedMaxX / 8 + 64 * kTilesWaves - 1) / (64 * kTilesWaves);
+
+__device__ __forceinline__ u32x4 ldw(const u32x4* p) { return __builtin_nontemporal_load(p); }
+
+// NPW = d / 256: k-blocks of the model dimension per wave and tile.
+template <int NPW>
+__global__ void __launch_bounds__(64 * kTilesWaves, 4) decode_tiles_kernel(FfnArgs a, RoutedArgs ra) {
+  constexpr int WAVES = kTilesWaves;
+  constexpr int D = NPW < 8 ? NPW : 8;     // ring depth: divides the per-tile and per-k-block item counts
+  __shared__ float red[WAVES * 2 * 256];   // prologue scratch, then [tile][gate|up][wave][16 rows]
+  __shared__ __align__(16) uint16_t hk[kTilesMaxT / 2 + 1][32];   // h of the workgroup's k-blocks, zero outside its rows
+  __shared__ RoutedLds rl;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+  // A shared expert (group K and up of a one-token call) runs whatever the router says: its workgroups skip the
+  // prologue and stream while the others still route - for that long the memory system is theirs alone.
+  const int g = blockIdx.y;
+  const bool always_on = g >= ra.a.K && g < a.g_max;
+  GroupView gv;
+  u32x4 xv[kXv];
+  if (always_on) {
+    gv.buf = a.P + (g - ra.a.K); gv.begin = g; gv.count = 1; gv.miss = 0; gv.expert = -1;
+#pragma unroll
+    for (int i = 0; i < kXv; ++i) {
+      const int v = threadIdx.x + i * 64 * WAVES;
+      xv[i] = v < a.d / 8 ? static_cast<const u32x4*>(a.x)[v] : u32x4{0, 0, 0, 0};
+    }
+  } else if (!routed_prologue<WAVES>(a, ra, rl, red, gv)) {
+    return;
+  }
+
+  const int n = lane & 15, q = lane >> 4;
+  const int d = a.d;
+  const int nkb_d = d >> 5, n_dt = d >> 4;
+  const int w = blockIdx.x, n_parts = a.n_parts;
+  const int F16 = a.f >> 4;
+  const int t0 = (int)((int64_t)w * F16 / n_parts), t1 = (int)((int64_t)(w + 1) * F16 / n_parts);
+  const int T = t1 - t0;
+  const int kb_lo = t0 >> 1, nkB = ((t1 - 1) >> 1) - kb_lo + 1;
+  const bool lo_cut = (t0 & 1) != 0, hi_cut = (t1 & 1) != 0;   // first / last k-block shared with a neighbour
+
+  const bool from_host = a.fetch != 0 && gv.miss != 0;
+  const char* wdev = gv.buf < a.P ? a.buffers + (size_t)gv.buf * a.expert_bytes
+                                  : a.shared + (size_t)(gv.buf - a.P) * a.expert_bytes;
+  const char* wsrc = from_host ? a.pool + (size_t)gv.expert * a.expert_bytes : wdev;
+  const intptr_t fill_delta = reinterpret_cast<intptr_t>(wdev) - reinterpret_cast<intptr_t>(wsrc);
+  const u32x4* wbase = reinterpret_cast<const u32x4*>(wsrc);
+  auto fill = [&](const u32x4* src, u32x4 v) {
+    *reinterpret_cast<u32x4*>(reinterpret_cast<intptr_t>(src) + fill_delta) = v;
+  };
+  // gate/up fragment (tile, kb, m) sits at ((tile * nkb_d + kb) * 2 + m) KiB: item i of the wave = (tile t0 + i / NPW,
+  // k-block wave + 8 (i % NPW)) is 16 KiB behind item i - 1.  W_d fragment (k-block, row tile) at (kb * n_dt + rt) KiB.
+  const u32x4* wa = wbase + ((size_t)t0 * nkb_d + wave) * 128 + lane;
+  const u32x4* wb = wbase + (size_t)2 * a.f * d / 8 + ((size_t)kb_lo * n_dt + wave) * 64 + lane;
+  const int na = T * NPW, nb = nkB * 2 * NPW, total = na + nb;     // gate/up items, W_d items of a wave
+
+  u32x4 sg[D], su[D];
+  int kkI = 0, jI = 0;      // phase-B item the next issue loads: row tile wave + 8 jI, k-block kb_lo + kkI
+  auto half_ok = [&](int kk) { return !((kk == 0 && lo_cut && q < 2) || (kk == nkB - 1 && hi_cut && q >= 2)); };
+  auto issue = [&](int slot, int item) {      // called with item = 0, 1, 2, ... in this order
+    if (item < na) {
+      sg[slot] = ldw(wa + (size_t)item * 1024);
+      su[slot] = ldw(wa + (size_t)item * 1024 + 64);
+    } else if (item < total) {
+      const u32x4* p = wb + ((size_t)kkI * n_dt + 8 * jI) * 64;
+      sg[slot] = half_ok(kkI) ? ldw(p) : u32x4{0, 0, 0, 0};
+      if (++kkI == nkB) { kkI = 0; ++jI; }
+    }
+  };
+#pragma unroll
+  for (int u = 0; u < D; ++u) issue(u, u);
+  if (always_on) {        // the token reaches LDS behind the first weight loads
+#pragma unroll
+    for (int i = 0; i < kXv; ++i) {
+      const int v = threadIdx.x + i * 64 * WAVES;
+      if (v < a.d / 8) rl.xs[v] = xv[i];
+    }
+    __syncthreads();
+  }
+
+  // ---- phase A ----
+  const uint16_t* xl = reinterpret_cast<const uint16_t*>(rl.xs) + (size_t)wave * 32 + q * 8;   // token 0, k-block `wave`
+  for (int t = 0; t < T; ++t) {
+    f32x4 accg = {0.f, 0.f, 0.f, 0.f}, accu = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NPW; ++i) {
+      const int u = i % D;
+      const bf16x8 xb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(xl + (size_t)i * 256));
+      accg = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, sg[u]), xb, accg, 0, 0, 0);
+      accu = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, su[u]), xb, accu, 0, 0, 0);
+      const int item = t * NPW + i;
+      if (from_host) {
+        fill(wa + (size_t)item * 1024, sg[u]);
+        fill(wa + (size_t)item * 1024 + 64, su[u]);
+      }
+      issue(u, item + D);
+    }
+    // every column of the B operand was token 0: the lanes of column 0 hold rows 4q .. 4q+3
+    if (n == 0) {
+      *reinterpret_cast<f32x4*>(&red[((t * 2 + 0) * WAVES + wave) * 16 + q * 4]) = accg;
+      *reinterpret_cast<f32x4*>(&red[((t * 2 + 1) * WAVES + wave) * 16 + q * 4]) = accu;
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < nkB * 32; i += 64 * WAVES) {
+    const int r16 = kb_lo * 32 + i;          // intermediate row
+    const int tt = (r16 >> 4) - t0, row = r16 & 15;
+    uint16_t hv = 0;
+    if (tt >= 0 && tt < T) {
+      float vg = 0.f, vu = 0.f;
+#pragma unroll
+      for (int k = 0; k < WAVES; ++k) {
+        vg += red[((tt * 2 + 0) * WAVES + k) * 16 + row];
+        vu += red[((tt * 2 + 1) * WAVES + k) * 16 + row];
+      }
+      hv = f32_to_bf16(silu(vg) * vu);
+    }
+    hk[i >> 5][i & 31] = hv;
+  }
+  __syncthreads();
+
+  // ---- phase B: items ordered (row tile, k-block); the ring slots continue where phase A stopped ----
+  float* obase = a.o + ((size_t)gv.begin * n_parts + w) * d + q * 4;
+  int kkC = 0, jC = 0;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  // (two W_d fragments per ring slot - as many bytes in flight as in phase A - was measured: 3 % slower)
+  for (int b0 = 0; b0 < nb; b0 += D) {
+#pragma unroll
+    for (int u = 0; u < D; ++u) {
+      const bf16x8 hb = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(&hk[kkC][q * 8]));
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, sg[u]), hb, acc, 0, 0, 0);
+      if (from_host && half_ok(kkC)) fill(wb + ((size_t)kkC * n_dt + 8 * jC) * 64, sg[u]);
+      issue(u, na + b0 + u + D);
+      if (++kkC == nkB) {       // uniform: the row tile is complete
+        if (n == 0) *reinterpret_cast<f32x4*>(obase + (size_t)(wave + WAVES * jC) * 16) = acc;
+        acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        kkC = 0;
+        ++jC;
+      }
+    }
+  }
+}
+
+int npw_of(int d) {
+  switch (d) {
+    case 256: return 1;
+    case 512: return 2;
+    case 1024: return 4;
+    case 2048: return 8;
+    case 4096: return 16;
+    default: return 0;
+  }
+}
+
+}  // namespace
+
+int decode_tiles_parts(int pool_layout, int d, int f, int batch, int groups, int n_cu, int E) {
+  if (pool_layout != MOE_LAYOUT_TILED || batch != 1 || groups <= 0 || groups > n_cu) return 0;
+  if (npw_of(d) == 0 || f % 32 != 0 || (E + 15) / 16 > 2 * kTilesWaves) return 0;
+  const int chunks = f / 32;
+  if (chunks * groups <= n_cu) return 0;      // the chunk kernel already has a compute unit per workgroup
+  const int n_parts = std::min(chunks, n_cu / groups);
+  const int f16 = f / 16, t_max = (f16 + n_parts - 1) / n_parts;
+  if (t_max > kTilesMaxT) return 0;
+  // Workgroups with one tile more than the others finish alone, at the rate of a single compute unit.  Up to
+  // 10 % above the mean the one-workgroup-per-unit launch still wins (Mixtral-like: 7 tiles each, 120 against
+  // 137 us; DeepSeekMoE-like: 2 or 3 of a mean 2.75); at 3 or 4 of a mean 3.125 (Phi-3.5-MoE-like) the chunk kernel,
+  // whose workgroups share the units dynamically, is 10 % faster.
+  if (t_max * n_parts * 10 > f16 * 11) return 0;
+  return n_parts;
+}
+
+hipError_t launch_decode_tiles(hipStream_t s, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev) {
+  dim3 grid(a.n_parts, a.g_max + 1), block(64 * kTilesWaves);     // + the bookkeeping row
+  switch (npw_of(a.d)) {
+    case 1: launch_timed(decode_tiles_kernel<1>, grid, block, 0, s, ev, a, ra); break;
+    case 2: launch_timed(decode_tiles_kernel<2>, grid, block, 0, s, ev, a, ra); break;
+    case 4: launch_timed(decode_tiles_kernel<4>, grid, block, 0, s, ev, a, ra); break;
+    case 8: launch_timed(decode_tiles_kernel<8>, grid, block, 0, s, ev, a, ra); break;
+    case 16: launch_timed(decode_tiles_kernel<16>, grid, block, 0, s, ev, a, ra); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace moe

@@ -108,6 +108,7 @@ struct moe_cache {
   char* router_packed = nullptr;       // [L] router matrices in operand order, for the single-launch decode
   bool single_ok = false;              // the single-launch decode kernel covers this cache's shape and policy
   int single_max_batch = 0;
+  int n_cu = 0;                        // compute units of the device
   Mailbox* call_log = nullptr;         // pinned, [kProfSlots]: call records of launches being timed
   CallTables t{};
   char* call_mem = nullptr;
@@ -600,6 +601,7 @@ int moe_cache_create(const moe_cache_config_t* cfg, const moe_weights_t* weights
       else break;
     c->single_ok = c->single_max_batch >= 1;
   }
+  CREATE_CHK(hipDeviceGetAttribute(&c->n_cu, hipDeviceAttributeMultiprocessorCount, c->device), MOE_ERR_HIP);
   if (c->single_ok) {
     CREATE_CHK(hipMalloc(&c->router_packed, router_packed_bytes(E, cfg->d_model) * L), MOE_ERR_HIP);
     CREATE_CHK(launch_pack_router(nullptr, weights->router_w, c->router_packed, E, cfg->d_model, L), MOE_ERR_HIP);
@@ -736,8 +738,11 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
     fa.fused = 1; fa.pass = 2;
     fa.pool = c->pool_dev[layer];
     fa.fetch = 1;
-    HIPCHK(launch_decode_single(s, cf.pool_layout, fa, q, ps ? ps->gate_up : KernelEvents{}));
-    HIPCHK(launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d, cf.d_ff / 32, y_dev, batch == 1));
+    fa.n_parts = decode_tiles_parts(cf.pool_layout, d, cf.d_ff, batch, fa.g_max, c->n_cu, E);
+    if (fa.n_parts > 0) HIPCHK(launch_decode_tiles(s, fa, q, ps ? ps->gate_up : KernelEvents{}));
+    else HIPCHK(launch_decode_single(s, cf.pool_layout, fa, q, ps ? ps->gate_up : KernelEvents{}));
+    HIPCHK(launch_combine_chunks(s, c->o, c->t.wpair, c->t.pos_of, batch, KS, d,
+                                 fa.n_parts > 0 ? fa.n_parts : cf.d_ff / 32, y_dev, batch == 1));
     c->cur[layer] ^= 1;
     c->dev_stats_used = true;
     c->stats[layer].lookups += (uint64_t)batch * K;

@@ -91,6 +91,7 @@ struct FfnArgs {
   int32_t pass;            // 0: groups whose buffer was resident, 1: groups fetched by this call, 2: all
   const char* pool;        // in-kernel fetch: this layer's expert blocks in pinned host memory (device-visible)
   int32_t fetch;           // 1: groups with miss == 1 read their weights from `pool` and fill their buffer
+  int32_t n_parts;         // tile kernel: workgroups (= partial rows in o) per group
 };
 
 // Router inputs of one call.
@@ -155,6 +156,10 @@ bool decode_single_supported(int pool_layout, int policy, int E, int C, int P, i
                              int batch);
 hipError_t launch_decode_single(hipStream_t s, int pool_layout, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev);
 hipError_t launch_decode_single_q4(hipStream_t s, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev);
+// Tile variant of the single-launch decode (one workgroup per compute unit, bf16 experts, one token): workgroups per
+// group it would use on a GPU of n_cu compute units, 0 when the chunk kernel is the one to launch.
+int decode_tiles_parts(int pool_layout, int d, int f, int batch, int groups, int n_cu, int E);
+hipError_t launch_decode_tiles(hipStream_t s, const FfnArgs& a, const RoutedArgs& ra, KernelEvents ev);
 int fused_q4_waves(int d);
 bool ffn_fused_q4_supported(int d, int f, int max_count);
 hipError_t launch_ffn_fused_q4(hipStream_t s, const FfnArgs& a, KernelEvents ev);

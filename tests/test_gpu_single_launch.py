@@ -36,7 +36,10 @@ def timing_counts(cache, fn):
 
 # experts, top-k, capacity, shared, d_model, d_ff: one and several logit tiles, shared experts, both wave counts
 SHAPES = [(16, 4, 6, 0, 256, 96), (8, 2, 3, 0, 512, 128), (64, 8, 16, 0, 256, 64), (40, 6, 12, 2, 256, 96),
-          (128, 4, 9, 0, 256, 64), (16, 2, 2, 1, 1024, 2048)]
+          (128, 4, 9, 0, 256, 64), (16, 2, 2, 1, 1024, 2048),
+          # more than 256 chunk workgroups per call: the tile kernel (one workgroup per compute unit, two or three
+          # 16-row tiles each, k-blocks shared between neighbours)
+          (16, 4, 6, 1, 256, 2400), (8, 2, 3, 0, 512, 5760), (16, 8, 10, 2, 1024, 1152)]
 
 
 @pytest.mark.parametrize("E,K,cap,ns,d,f", SHAPES)

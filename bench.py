@@ -430,7 +430,8 @@ def kernel_roofline(cfg, tm, traffic):
         k_bytes = experts + E * d * s_el + d * s_el + E * 4 + KS_ * d * 4
         k_ms = tm["decode_single_ms"] / tm["decode_single_launches"]
         k_n = tm["decode_single_launches"]
-        k_name = ("decode_single_kernel (router GEMV, Top-K gating, cache lookups and gate/up + SiLU*mul + down "
+        k_name = (("decode_tiles_kernel" if tm.get("decode_tiles_launches", 0) > 0 else "decode_single_kernel") +
+                  " (router GEMV, Top-K gating, cache lookups and gate/up + SiLU*mul + down "
                   "projection of the K selected experts in one launch)")
     elif tm["ffn_fused_launches"] > 0:
         k_bytes = experts + d * s_el + KS_ * d * 4
@@ -599,7 +600,8 @@ def measure(torch, P, wl, pool, a, steps, warmup, full):
                           "us_per_layer_call": 1e6 / res_tok_s / cfg.n_layers,
                           "algorithmic_GBps_whole_call": layer_bytes * cfg.n_layers * res_tok_s / 1e9,
                           "frac_of_hbm_peak_whole_call": layer_bytes * cfg.n_layers * res_tok_s / 1e9 / HBM_PEAK_GBPS,
-                          "launches_per_call": ("decode_single_kernel + combine_chunks_kernel"
+                          "launches_per_call": (("decode_tiles_kernel" if rtm.get("decode_tiles_launches", 0) else
+                                                 "decode_single_kernel") + " + combine_chunks_kernel"
                                                 if rtm["decode_single_launches"] else
                                                 "route_cache_kernel + expert FFN + combine"),
                           "main_kernel_us": (rtm["ffn_gate_up_ms"] + rtm["ffn_down_ms"] + rtm["ffn_fused_ms"] +

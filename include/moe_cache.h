@@ -163,6 +163,8 @@ typedef struct {
   uint64_t copies;       /* expert copies timed                                             */
   uint64_t copy_bytes;   /* bytes moved by them                                             */
   double copy_ms;        /* summed duration of the copy batches on the copy stream          */
+  uint64_t decode_tiles_launches; /* how many of decode_single_launches ran the tile kernel (one workgroup per
+                            compute unit, chosen for one-token calls on large experts) instead of the chunk kernel */
 } moe_timing_t;
 
 /* Bytes of one expert block for the given shape; 0 if the arguments are invalid. */

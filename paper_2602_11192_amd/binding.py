@@ -62,7 +62,8 @@ class moe_timing_t(C.Structure):
                 ("route_launches", C.c_uint64), ("route_ms", C.c_double),
                 ("fetch_launches", C.c_uint64), ("fetch_bytes", C.c_uint64), ("fetch_ms", C.c_double),
                 ("decode_single_launches", C.c_uint64), ("decode_single_ms", C.c_double),
-                ("copies", C.c_uint64), ("copy_bytes", C.c_uint64), ("copy_ms", C.c_double)]
+                ("copies", C.c_uint64), ("copy_bytes", C.c_uint64), ("copy_ms", C.c_double),
+                ("decode_tiles_launches", C.c_uint64)]
 
 
 class moe_resident_layer_t(C.Structure):

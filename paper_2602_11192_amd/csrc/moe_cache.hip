@@ -76,6 +76,7 @@ constexpr int kProfSlots = 512;
 struct ProfSlot {
   KernelEvents route, gate_up, down;   // attached to the dispatches of the three main kernels of a call
   bool used = false;
+  bool tiles = false;  // ... and it was the tile kernel
   bool single = false; // the call was one launch (router to combine, timed by `gate_up`); its record is in the call log
   bool mixed = false;  // the call also fetched experts: its resident-pass FFN covers only part of the K experts
   bool fused = false;  // the call used the single-launch decode FFN (timed by `gate_up`)
@@ -304,6 +305,7 @@ int drain_prof_slot(moe_cache* c, ProfSlot& p) {
     } else {
       c->timing.decode_single_ms += a;
       c->timing.decode_single_launches += 1;
+      c->timing.decode_tiles_launches += p.tiles ? 1 : 0;
     }
     p.used = false;
     return MOE_OK;
@@ -746,7 +748,7 @@ int decode_wave(moe_cache_t* c, int32_t layer, const void* x_dev, const float* l
     c->cur[layer] ^= 1;
     c->dev_stats_used = true;
     c->stats[layer].lookups += (uint64_t)batch * K;
-    if (ps) { ps->used = true; ps->single = true; ps->fused = true; ps->mixed = false; ps->fetched = 0; }
+    if (ps) { ps->used = true; ps->single = true; ps->tiles = fa.n_parts > 0; ps->fused = true; ps->mixed = false; ps->fetched = 0; }
     return MOE_OK;
   }
 

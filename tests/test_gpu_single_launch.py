@@ -60,6 +60,8 @@ def test_batch1_constrained_cache(torch, P, E, K, cap, ns, d, f, pins):
     y = torch.empty((1, d), dtype=torch.bfloat16, device="cuda:0")
     tm = timing_counts(cache, lambda: [cache.moe_layer_decode(0, x, y) for _ in range(4)])
     assert tm["decode_single_launches"] + tm["fetch_launches"] == 4 and tm["route_launches"] == 0
+    # more chunk workgroups than compute units: the resident calls among them ran the tile kernel
+    assert tm["decode_tiles_launches"] == (tm["decode_single_launches"] if (f // 32) * (K + ns) > 256 else 0)
     cache.close()
 
 

@@ -349,7 +349,11 @@ int moe_cache_sim_loss(const int32_t* idx_dev, int32_t n_traces, int32_t T, int3
  *              router_w [E][d], experts [E] expert blocks in `pool_layout` (expert e at byte e *
  *              moe_expert_block_bytes()), shared_w [n_shared] blocks or NULL iff n_shared == 0
  *   other arguments as for moe_layer_decode; the device is the calling thread's current device.
- * Outputs equal those of moe_layer_decode on a cache of capacity E preloaded with experts 0..E-1 in that order.
+ * topk_idx and topk_w equal those of moe_layer_decode on a cache of capacity E preloaded with experts 0..E-1 in
+ * that order; y equals it up to the order in which the fp32 partial sums of an expert are added: bit for bit when
+ * both entry points run the same expert kernel, within the last bf16 digit otherwise (one-token calls on shapes that
+ * moe_layer_decode hands to its tile kernel; batches that this entry point runs through the grouped GEMM so that its
+ * partial sums fit the array).
  * Nothing is counted or traced.  A batch whose tables and partial sums exceed the array is rejected with
  * MOE_ERR_UNSUPPORTED (the message names the bytes needed).  All calls on one GPU share the array: calls that
  * overlap in time on one GPU (different streams without ordering, different threads) race.

@@ -88,14 +88,15 @@ def test_small_batches_on_a_cache_that_holds_everything(torch, P, batch, E, K, n
     cache.close()
 
 
-def test_results_do_not_depend_on_timing(torch, P):
-    """The in-launch reduction adds the partial sums in a fixed order: repeated calls give identical bits."""
+@pytest.mark.parametrize("E,K,d,f", [(64, 8, 2048, 1024), (8, 2, 512, 5760)], ids=["chunk kernel", "tile kernel"])
+def test_results_do_not_depend_on_timing(torch, P, E, K, d, f):
+    """The partial sums are added in a fixed order (in LDS, then by the combine): repeated calls give identical bits."""
     B = P.B
-    cfg = small_cfg(n_experts=64, top_k=8, capacity=64, d_model=2048, d_ff=1024, n_layers=1, n_seqs=2, n_steps=2,
+    cfg = small_cfg(n_experts=E, top_k=K, capacity=E, d_model=d, d_ff=f, n_layers=1, n_seqs=2, n_steps=2,
                     cfg_id=43)
     wl = Workload(cfg)
     cache = P.make_cache(wl, tiled=True, fetch_mode=B.MOE_FETCH_IN_KERNEL)
-    cache.moe_cache_prefill_pins(0, list(range(64)))
+    cache.moe_cache_prefill_pins(0, list(range(E)))
     x = P.to_device(wl.tokens(0)[:1])
     ys = []
     for _ in range(20):
@@ -105,7 +106,7 @@ def test_results_do_not_depend_on_timing(torch, P):
     torch.cuda.synchronize()
     for y in ys[1:]:
         assert torch.equal(y.view(torch.int16), ys[0].view(torch.int16))
-    ost = OracleStack(wl, capacity=64, keep=64)
+    ost = OracleStack(wl, capacity=E, keep=E)
     res = ost.decode(0, widen(wl.tokens(0)[:1]), None)
     assert float(rel_err(P.to_numpy(ys[0]), res.y)[0]) <= TOL["bf16"]
     cache.close()

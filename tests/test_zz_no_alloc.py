@@ -84,6 +84,48 @@ def test_noalloc_equals_cached_decode(torch, P, name, cfg, tiled, int4, batches)
     cache.close()
 
 
+def test_noalloc_beside_the_tile_kernel(torch, P):
+    """A one-token call on large experts: the cached decode runs its tile kernel, this entry point the chunk kernel.
+    Same routing bit for bit; the outputs differ at most by the order of the fp32 partial sums."""
+    B = P.B
+    cfg = cfg_of(cfg_id=37, d_model=512, d_ff=5760, n_experts=8, top_k=2, capacity=8, n_seqs=4, pref_lo=2, pref_hi=2)
+    wl = Workload(cfg)
+    E, K, d = cfg.n_experts, cfg.top_k, cfg.d_model
+    pool = P.build_pool(wl, True)
+    experts_dev = pool.cuda()
+    router = P.build_router(wl)
+    cache = P.make_cache(wl, tiled=True, pool=pool, capacity=E, fetch_mode=B.MOE_FETCH_IN_KERNEL)
+    cache.moe_cache_prefill_pins(0, list(range(E)))
+    ost = OracleStack(wl, capacity=E)
+    for s in range(cfg.n_seqs):
+        print("noalloc beside the tile kernel, sequence %d" % s, flush=True)
+        tok = wl.tokens(s)[:1]
+        x = P.to_device(tok)
+        y0 = torch.empty((1, d), dtype=torch.bfloat16, device="cuda:0")
+        y1 = torch.full((1, d), 7.0, dtype=torch.bfloat16, device="cuda:0")
+        i0 = torch.empty((1, K), dtype=torch.int32, device="cuda:0")
+        i1 = torch.full((1, K), -1, dtype=torch.int32, device="cuda:0")
+        w0 = torch.empty((1, K), dtype=torch.float32, device="cuda:0")
+        w1 = torch.full((1, K), -1.0, dtype=torch.float32, device="cuda:0")
+        cache.moe_cache_set_profiling(True)
+        cache.moe_cache_timing(clear=True)
+        cache.moe_layer_decode(0, x, y0, None, i0, w0)
+        tm = cache.moe_cache_timing(clear=True)
+        cache.moe_cache_set_profiling(False)
+        assert tm["decode_tiles_launches"] == 1
+        B.moe_layer_decode_resident_noalloc(
+            n_experts=E, n_shared=0, top_k=K, d_model=d, d_ff=cfg.d_ff, dtype=P.moe_dtype(cfg),
+            norm_topk=cfg.norm_topk, pool_layout=B.MOE_LAYOUT_TILED, router_w=router, experts=experts_dev,
+            shared_w=None, x=x, y=y1, logit_bias=None, topk_idx=i1, topk_w=w1)
+        torch.cuda.synchronize()
+        assert torch.equal(i0, i1) and torch.equal(w0, w1)
+        res = ost.decode(0, widen(tok), None)
+        assert float(rel_err(P.to_numpy(y0), res.y).max()) <= TOL["bf16"]
+        assert float(rel_err(P.to_numpy(y1), res.y).max()) <= TOL["bf16"]
+        assert float(rel_err(P.to_numpy(y1), P.to_numpy(y0).astype(np.float64)).max()) <= TOL["bf16"]
+    cache.close()
+
+
 def test_noalloc_rejects_what_does_not_fit(torch, P):
     B = P.B
     cfg = cfg_of(cfg_id=36)

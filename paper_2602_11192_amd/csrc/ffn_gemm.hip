@@ -14,6 +14,8 @@
 // spread thinly over many experts degrades into weight streaming rather than
 // wasted matrix work.  NMAT = 2 computes h = silu(X W_g^T) * (X W_u^T) (bf16,
 // rows in group order); NMAT = 1 computes o = h W_d^T (fp32).
+#include <type_traits>
+
 #include "device_utils.hpp"
 #include "moe_internal.hpp"
 
@@ -58,7 +60,14 @@ __device__ __forceinline__ const char* group_weights(const FfnArgs& a, int id) {
 // kSkb: k-blocks staged per step.  The default (two for gate/up, one for the down pass) suits launches with many
 // workgroups per compute unit; a down pass with few workgroups and a long contraction (Mixtral-like: 512
 // workgroups, 448 k-blocks) is bound by the latency of its one-KiB-per-wave steps and takes four k-blocks per step.
-template <int NMAT, int kTokTile, int kGemmWaves, int kSkb = kStageKbOf<NMAT>>
+// kRing: stages of weight fragments a wave keeps in flight.  1: the next stage is requested while the current one
+// multiplies (and the compiler waits for it at the end of the stage).  More: a ring with fixed slots, the stage loop
+// unrolled kRing times, every load unconditional and the tokens requested ahead of the weights, so that waiting for
+// the tokens of the next stage does not mean waiting for weights that are needed three stages later; the host
+// picks it only when the number of stages is a multiple of kRing.
+// kList: the (group, token tile) pairs come from the call's work list (gemm_worklist_kernel below) instead of the grid:
+// blockIdx.y is an index into the list.
+template <int NMAT, int kTokTile, int kGemmWaves, int kSkb = kStageKbOf<NMAT>, int kRing = 1, bool kList = false>
 __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   constexpr int kGemmThreads = 64 * kGemmWaves;
   constexpr int kColBlocks = kTokTile / 16;
@@ -68,11 +77,20 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   constexpr bool kExact = kTotalPieces % kGemmThreads == 0;   // every thread stages kPieces pieces     // 16-byte pieces of the token tile each thread stages per step
   // [buffer][k-block in stage][column block][lane] x 16 bytes
   __shared__ u32x4 xs[2][kStageKb][kColBlocks][64];
-  const int g = blockIdx.y;
-  const int ng = *a.t.n_groups;
+  int g, tok0;
+  if constexpr (kList) {
+    const int32_t* list = a.t.pair_buf;
+    if ((int)blockIdx.y >= list[NMAT == 2 ? 0 : 1]) return;
+    const int item = list[2 + (NMAT == 2 ? 0 : a.work_down) + blockIdx.y];
+    g = item & 0xffff;
+    tok0 = (item >> 16) * kTokTile;
+  } else {
+    g = blockIdx.y;
+    tok0 = blockIdx.z * kTokTile;
+    if (g >= *a.t.n_groups) return;
+  }
   const GroupDesc gd = a.t.grp[g];
-  if (g >= ng || (a.pass != 2 && gd.miss != a.pass)) return;
-  const int tok0 = blockIdx.z * kTokTile;
+  if (a.pass != 2 && gd.miss != a.pass) return;
   const int cnt = gd.count;
   if (tok0 >= cnt) return;
   const int n_tok = min(kTokTile, cnt - tok0);       // tokens of this tile
@@ -143,6 +161,80 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
 #pragma unroll
     for (int m = 0; m < NMAT; ++m) acc[cb][m] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+  if constexpr (kRing > 1) {
+    constexpr int R = kRing;
+    const int n_stages = nkb / kStageKb;            // a multiple of R (host)
+    // pieces outside the tile read the first piece's address (always valid) and are zeroed on the way to LDS
+    const uint16_t* srcv[kPieces];
+    bool xok[kPieces];
+#pragma unroll
+    for (int i = 0; i < kPieces; ++i) {
+      xok[i] = src[i] != nullptr;
+      srcv[i] = xok[i] ? src[i] : reinterpret_cast<const uint16_t*>(NMAT == 2 ? a.x : a.h);
+    }
+    u32x4 xq[R][kPieces], wr[R][kStageKb][NMAT];
+    auto req_x = [&](int slot, int s) {
+      const int sc = s < n_stages ? s : n_stages - 1;
+#pragma unroll
+      for (int i = 0; i < kPieces; ++i)
+        xq[slot][i] = *reinterpret_cast<const u32x4*>(srcv[i] + (size_t)sc * kStageKb * 32);
+    };
+    auto req_w = [&](int slot, int s) {
+      const int sc = s < n_stages ? s : n_stages - 1;
+#pragma unroll
+      for (int j = 0; j < kStageKb; ++j)
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m)
+          wr[slot][j][m] = __builtin_nontemporal_load(w + (size_t)(sc * kStageKb + j) * kb_stride + m * 64);
+    };
+    auto put_x = [&](int b, int slot) {
+#pragma unroll
+      for (int i = 0; i < kPieces; ++i)
+        if (kExact || dst[i] >= 0) (&xs[b][0][0][0])[dst[i]] = xok[i] ? xq[slot][i] : u32x4{0, 0, 0, 0};
+    };
+    // tokens and weights of stage s are requested R - 1 stages before they are used
+#pragma unroll
+    for (int u = 0; u < R - 1; ++u) {
+      req_x(u, u);
+      req_w(u, u);
+    }
+    put_x(0, 0);
+    __syncthreads();
+    // the column blocks in use, rounded up to a quarter of the tile, as a compile-time count: no branch inside the
+    // stage loop (column blocks beyond the tile's tokens hold zeros)
+    auto run = [&](auto ncb_tag) {
+      constexpr int NCB = decltype(ncb_tag)::value;
+#pragma unroll 1
+      for (int s0 = 0; s0 < n_stages; s0 += R) {
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+          const int s = s0 + u;
+          req_x((u + R - 1) % R, s + R - 1);  // tokens first: older than the weights requested next
+          req_w((u + R - 1) % R, s + R - 1);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int j = 0; j < kStageKb; ++j) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+              const bf16x8 bfrag = __builtin_bit_cast(bf16x8, xs[u & 1][j][cb][lane ^ swz<kStageKb>(lane >> 4, j)]);
+#pragma unroll
+              for (int m = 0; m < NMAT; ++m)
+                acc[cb][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[u][j][m]), bfrag,
+                                                                     acc[cb][m], 0, 0, 0);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          put_x((u & 1) ^ 1, (u + 1) % R);      // stage s + 1, requested two stages ago
+          __syncthreads();
+        }
+      }
+    };
+    constexpr int Q = kColBlocks / 4;
+    if (n_cb <= Q) run(std::integral_constant<int, Q>{});
+    else if (n_cb <= 2 * Q) run(std::integral_constant<int, 2 * Q>{});
+    else if (n_cb <= 3 * Q) run(std::integral_constant<int, 3 * Q>{});
+    else run(std::integral_constant<int, kColBlocks>{});
+  } else {
   u32x4 xr[kPieces], wc[kStageKb][NMAT], wn[kStageKb][NMAT];
   load_x(xr, 0);
   load_w(wc, 0);
@@ -183,6 +275,7 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
     __syncthreads();
     buf ^= 1;
   }
+  }
 
   // ---- epilogue: lane holds rows (lane/16)*4 .. +3 of the row tile for token column lane%16 ----
   if (!has_rows) return;
@@ -204,6 +297,44 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
         *reinterpret_cast<f32x4*>(a.o + pos * a.d + rt * 16 + r4) = acc[cb][0];
       }
     }
+  }
+}
+
+// The work list of a large call: one item per (group, token tile) that exists, groups with the most tokens first, for
+// the gate/up pass (tiles of tile_up tokens) and for the down pass (tile_down).  Launching a grid of groups x the
+// largest possible tile count instead leaves most workgroups empty (each still waits for its group record before it
+// can tell), and the second and third tiles of the busy experts start last, a few dozen workgroups on an idle GPU
+// (per-workgroup time stamps at 1024 tokens per call: 31 ms of workgroup time packed into 175 us on 256 units
+// instead of 122).  The list lives in pair_buf, which nothing reads once the pairs are grouped:
+// [0] items of the gate/up pass, [1] of the down pass, [2 ...) gate/up items, [2 + work_down ...) down items;
+// item = group | tile << 16.  One workgroup of 256 threads; at most 256 groups.
+__global__ void __launch_bounds__(256) gemm_worklist_kernel(CallTables t, int tile_up, int tile_down, int work_down) {
+  __shared__ int s_cnt[256], s_first_up[256], s_first_down[256];
+  const int ng = *t.n_groups;
+  const int g = threadIdx.x;
+  const int cnt = g < ng ? t.grp[g].count : 0;
+  s_cnt[g] = cnt;
+  __syncthreads();
+  // position of the group when sorted by token count, largest first (ties by group index)
+  int rank = 0;
+  for (int j = 0; j < ng; ++j) rank += (s_cnt[j] > cnt || (s_cnt[j] == cnt && j < g)) ? 1 : 0;
+  const int nu = (cnt + tile_up - 1) / tile_up, nd = (cnt + tile_down - 1) / tile_down;
+  if (g < ng) { s_first_up[rank] = nu; s_first_down[rank] = nd; }
+  __syncthreads();
+  if (threadIdx.x == 0) {       // exclusive prefix sums in rank order (at most 256 short steps)
+    int au = 0, ad = 0;
+    for (int r = 0; r < ng; ++r) {
+      const int u = s_first_up[r], d = s_first_down[r];
+      s_first_up[r] = au; s_first_down[r] = ad;
+      au += u; ad += d;
+    }
+    t.pair_buf[0] = au;
+    t.pair_buf[1] = ad;
+  }
+  __syncthreads();
+  if (g < ng) {
+    for (int i = 0; i < nu; ++i) t.pair_buf[2 + s_first_up[rank] + i] = g | (i << 16);
+    for (int i = 0; i < nd; ++i) t.pair_buf[2 + work_down + s_first_down[rank] + i] = g | (i << 16);
   }
 }
 
@@ -232,9 +363,23 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, Ker
     return dim3((rows / 16 + wv - 1) / wv, a.g_max, (a.max_count + tok_tile - 1) / tok_tile);
   };
   const dim3 b4(64 * 4), b8(64 * 8);
+  // Large calls (measured on the OLMoE-like layer, gate/up + down: 188 against 200 us at 448 tokens per call, 193
+  // against 210 at 512, 262 against 281 at 1024, 399 against 475 at 2048; level at 384, slower below): the ring
+  // variant on 128-token tiles, its workgroups taken from a work list, for the gate/up pass from a mean of 40 pairs
+  // per group, for the down pass from 56.
+  constexpr int kRingUp = 40, kRingDown = 56, kRingTile = 128;
+  const int cap = a.g_max + (int)(load / kRingTile);        // upper bound on the items of either list
+  const bool listed = waves == 8 && a.g_max <= 256 && load >= (int64_t)kRingUp * a.g_max && 2 + 2 * cap <= load;
+  const bool ring_up = listed && a.d % 256 == 0;                 // stages of two k-blocks, a multiple of four of them
+  const bool ring_down = listed && load >= (int64_t)kRingDown * a.g_max && a.f % 128 == 0;
+  FfnArgs b = a;
+  b.work_down = cap;
+  if (ring_up || ring_down)
+    hipLaunchKernelGGL(gemm_worklist_kernel, dim3(1), dim3(256), 0, s, a.t, kRingTile, kRingTile, cap);
   // ---- gate/up ----
   if (small_tile) launch_timed(ffn_gemm_kernel<2, 64, 4>, grid(a.f, 64, 4), b4, 0, s, e1, a);
   else if (waves == 4) launch_timed(ffn_gemm_kernel<2, 128, 4>, grid(a.f, 128, 4), b4, 0, s, e1, a);
+  else if (ring_up) launch_timed(ffn_gemm_kernel<2, kRingTile, 8, 2, 4, true>, dim3((a.f / 16 + 7) / 8, cap), b8, 0, s, e1, b);
   else if (big_up) launch_timed(ffn_gemm_kernel<2, 256, 8>, grid(a.f, 256, 8), b8, 0, s, e1, a);
   else launch_timed(ffn_gemm_kernel<2, 128, 8>, grid(a.f, 128, 8), b8, 0, s, e1, a);
   // ---- down ----
@@ -246,6 +391,7 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, Ker
   if (deep_down) launch_timed(ffn_gemm_kernel<1, 64, 4, 4>, grid(a.d, 64, 4), b4, 0, s, e2, a);
   else if (small_tile) launch_timed(ffn_gemm_kernel<1, 64, 4>, grid(a.d, 64, 4), b4, 0, s, e2, a);
   else if (waves == 4) launch_timed(ffn_gemm_kernel<1, 128, 4>, grid(a.d, 128, 4), b4, 0, s, e2, a);
+  else if (ring_down) launch_timed(ffn_gemm_kernel<1, kRingTile, 8, 1, 4, true>, dim3((a.d / 16 + 7) / 8, cap), b8, 0, s, e2, b);
   else if (big_down) launch_timed(ffn_gemm_kernel<1, 256, 8>, grid(a.d, 256, 8), b8, 0, s, e2, a);
   else launch_timed(ffn_gemm_kernel<1, 128, 8>, grid(a.d, 128, 8), b8, 0, s, e2, a);
   return hipGetLastError();

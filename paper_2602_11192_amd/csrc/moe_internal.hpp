@@ -92,6 +92,7 @@ struct FfnArgs {
   const char* pool;        // in-kernel fetch: this layer's expert blocks in pinned host memory (device-visible)
   int32_t fetch;           // 1: groups with miss == 1 read their weights from `pool` and fill their buffer
   int32_t n_parts;         // tile kernel: workgroups (= partial rows in o) per group
+  int32_t work_down;       // grouped GEMM with a work list: offset of the down pass's items in the list (0: no list)
 };
 
 // Router inputs of one call.

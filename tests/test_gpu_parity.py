@@ -201,12 +201,15 @@ def test_resident_batch_with_64_buffers_and_shared_experts(torch, P):
     cache.close()
 
 
+@pytest.mark.parametrize("d_model,d_ff", [(160, 96), (256, 128), (512, 96)])
 @pytest.mark.parametrize("n_experts,top_k,batch", [(16, 4, 128), (4, 2, 300), (8, 2, 97), (2, 1, 520), (8, 2, 600)])
-def test_many_tokens_per_expert_take_the_grouped_gemm(torch, P, n_experts, top_k, batch):
+def test_many_tokens_per_expert_take_the_grouped_gemm(torch, P, n_experts, top_k, batch, d_model, d_ff):
     # enough tokens per expert for the LDS-staged grouped GEMM: 64- and 128-token tiles, and from ~100 tokens per
-    # expert the 256-token tiles (300 tokens over 4 experts, 520 over 2: several tiles per expert, ragged last tile)
+    # expert the 256-token tiles (300 tokens over 4 experts, 520 over 2: several tiles per expert, ragged last tile).
+    # d_model a multiple of 256 / d_ff of 128: from a mean of 40 / 56 tokens per expert the gate/up / down pass runs the
+    # ring variant on a work list (both at 256 x 128, only the gate/up pass at 512 x 96)
     cfg = small_cfg(n_experts=n_experts, top_k=top_k, capacity=n_experts, n_seqs=batch, n_steps=2, n_layers=1,
-                    d_model=160, d_ff=96, n_shared=1, pref_lo=1, pref_hi=1)
+                    d_model=d_model, d_ff=d_ff, n_shared=1, pref_lo=1, pref_hi=1)
     wl = Workload(cfg)
     cache = P.make_cache(wl, tiled=True, max_batch=batch, trace_capacity=4096)
     ost = OracleStack(wl, capacity=n_experts, keep=n_experts)

@@ -77,19 +77,25 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   constexpr bool kExact = kTotalPieces % kGemmThreads == 0;   // every thread stages kPieces pieces     // 16-byte pieces of the token tile each thread stages per step
   // [buffer][k-block in stage][column block][lane] x 16 bytes
   __shared__ u32x4 xs[2][kStageKb][kColBlocks][64];
-  int g, tok0;
+  int tok0;
+  GroupDesc gd;
   if constexpr (kList) {
+    // the item carries what the workgroup needs of its group: one memory round trip instead of two before the
+    // first weight request (the index is below the list's capacity, so the load needs no guard)
     const int32_t* list = a.t.pair_buf;
-    if ((int)blockIdx.y >= list[NMAT == 2 ? 0 : 1]) return;
-    const int item = list[2 + (NMAT == 2 ? 0 : a.work_down) + blockIdx.y];
-    g = item & 0xffff;
-    tok0 = (item >> 16) * kTokTile;
+    const int n_items = list[NMAT == 2 ? 0 : 1];
+    const int4 item = reinterpret_cast<const int4*>(list + 4)[(NMAT == 2 ? 0 : a.work_down) + blockIdx.y];
+    if ((int)blockIdx.y >= n_items) return;
+    tok0 = (item.x >> 16) * kTokTile;
+    gd.buf = item.y; gd.begin = item.z; gd.count = item.w & 0x3fffffff; gd.miss = (item.w >> 30) & 1;
+    gd.expert = -1; gd.pair0 = 0;
   } else {
-    g = blockIdx.y;
+    const int g = blockIdx.y;
     tok0 = blockIdx.z * kTokTile;
-    if (g >= *a.t.n_groups) return;
+    const int ng = *a.t.n_groups;
+    gd = a.t.grp[g];
+    if (g >= ng) return;
   }
-  const GroupDesc gd = a.t.grp[g];
   if (a.pass != 2 && gd.miss != a.pass) return;
   const int cnt = gd.count;
   if (tok0 >= cnt) return;
@@ -116,6 +122,23 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
   } else {
     w += (size_t)2 * a.f * a.d / 8 + (size_t)rtc * 64 + lane;
     kb_stride = (size_t)(a.d >> 4) * 64;
+  }
+
+  // ring variant: the first weight stages are requested before the token addresses are looked up
+  constexpr int kRingSlots = kRing > 1 ? kRing : 1;
+  u32x4 wr[kRingSlots][kStageKb][NMAT];
+  const int n_stages = nkb / kStageKb;            // ring variant: a multiple of kRing (host)
+  auto req_w = [&](int slot, int s) {
+    const int sc = s < n_stages ? s : n_stages - 1;
+#pragma unroll
+    for (int j = 0; j < kStageKb; ++j)
+#pragma unroll
+      for (int m = 0; m < NMAT; ++m)
+        wr[slot][j][m] = __builtin_nontemporal_load(w + (size_t)(sc * kStageKb + j) * kb_stride + m * 64);
+  };
+  if constexpr (kRing > 1) {
+#pragma unroll
+    for (int u = 0; u < kRing - 1; ++u) req_w(u, u);
   }
 
   // ---- staging assignment: 256 threads x kPieces pieces of 16 bytes = 128 rows x kStageKb k-blocks of 64 bytes ----
@@ -163,7 +186,6 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
 
   if constexpr (kRing > 1) {
     constexpr int R = kRing;
-    const int n_stages = nkb / kStageKb;            // a multiple of R (host)
     // pieces outside the tile read the first piece's address (always valid) and are zeroed on the way to LDS
     const uint16_t* srcv[kPieces];
     bool xok[kPieces];
@@ -172,20 +194,12 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
       xok[i] = src[i] != nullptr;
       srcv[i] = xok[i] ? src[i] : reinterpret_cast<const uint16_t*>(NMAT == 2 ? a.x : a.h);
     }
-    u32x4 xq[R][kPieces], wr[R][kStageKb][NMAT];
+    u32x4 xq[R][kPieces];
     auto req_x = [&](int slot, int s) {
       const int sc = s < n_stages ? s : n_stages - 1;
 #pragma unroll
       for (int i = 0; i < kPieces; ++i)
         xq[slot][i] = *reinterpret_cast<const u32x4*>(srcv[i] + (size_t)sc * kStageKb * 32);
-    };
-    auto req_w = [&](int slot, int s) {
-      const int sc = s < n_stages ? s : n_stages - 1;
-#pragma unroll
-      for (int j = 0; j < kStageKb; ++j)
-#pragma unroll
-        for (int m = 0; m < NMAT; ++m)
-          wr[slot][j][m] = __builtin_nontemporal_load(w + (size_t)(sc * kStageKb + j) * kb_stride + m * 64);
     };
     auto put_x = [&](int b, int slot) {
 #pragma unroll
@@ -194,10 +208,7 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
     };
     // tokens and weights of stage s are requested R - 1 stages before they are used
 #pragma unroll
-    for (int u = 0; u < R - 1; ++u) {
-      req_x(u, u);
-      req_w(u, u);
-    }
+    for (int u = 0; u < R - 1; ++u) req_x(u, u);
     put_x(0, 0);
     __syncthreads();
     // the column blocks in use, rounded up to a quarter of the tile, as a compile-time count: no branch inside the
@@ -306,13 +317,16 @@ __global__ void __launch_bounds__(64 * kGemmWaves) ffn_gemm_kernel(FfnArgs a) {
 // can tell), and the second and third tiles of the busy experts start last, a few dozen workgroups on an idle GPU
 // (per-workgroup time stamps at 1024 tokens per call: 31 ms of workgroup time packed into 175 us on 256 units
 // instead of 122).  The list lives in pair_buf, which nothing reads once the pairs are grouped:
-// [0] items of the gate/up pass, [1] of the down pass, [2 ...) gate/up items, [2 + work_down ...) down items;
-// item = group | tile << 16.  One workgroup of 256 threads; at most 256 groups.
+// [0] items of the gate/up pass, [1] of the down pass, then 16-byte items from [4] on: gate/up items, and from item
+// work_down on the down items; item = (group | tile << 16, buffer, begin, count | miss << 30): what a workgroup needs
+// of its group record, so that it does not have to fetch that as well.  One workgroup of 256 threads, at most 256 groups.
 __global__ void __launch_bounds__(256) gemm_worklist_kernel(CallTables t, int tile_up, int tile_down, int work_down) {
   __shared__ int s_cnt[256], s_first_up[256], s_first_down[256];
   const int ng = *t.n_groups;
   const int g = threadIdx.x;
-  const int cnt = g < ng ? t.grp[g].count : 0;
+  GroupDesc gd{};
+  if (g < ng) gd = t.grp[g];
+  const int cnt = gd.count;
   s_cnt[g] = cnt;
   __syncthreads();
   // position of the group when sorted by token count, largest first (ties by group index)
@@ -333,8 +347,10 @@ __global__ void __launch_bounds__(256) gemm_worklist_kernel(CallTables t, int ti
   }
   __syncthreads();
   if (g < ng) {
-    for (int i = 0; i < nu; ++i) t.pair_buf[2 + s_first_up[rank] + i] = g | (i << 16);
-    for (int i = 0; i < nd; ++i) t.pair_buf[2 + work_down + s_first_down[rank] + i] = g | (i << 16);
+    int4* items = reinterpret_cast<int4*>(t.pair_buf + 4);
+    const int w3 = cnt | ((gd.miss != 0 ? 1 : 0) << 30);
+    for (int i = 0; i < nu; ++i) items[s_first_up[rank] + i] = int4{g | (i << 16), gd.buf, gd.begin, w3};
+    for (int i = 0; i < nd; ++i) items[work_down + s_first_down[rank] + i] = int4{g | (i << 16), gd.buf, gd.begin, w3};
   }
 }
 
@@ -369,7 +385,7 @@ hipError_t launch_ffn_gemm(hipStream_t s, const FfnArgs& a, KernelEvents e1, Ker
   // per group, for the down pass from 56.
   constexpr int kRingUp = 40, kRingDown = 56, kRingTile = 128;
   const int cap = a.g_max + (int)(load / kRingTile);        // upper bound on the items of either list
-  const bool listed = waves == 8 && a.g_max <= 256 && load >= (int64_t)kRingUp * a.g_max && 2 + 2 * cap <= load;
+  const bool listed = waves == 8 && a.g_max <= 256 && load >= (int64_t)kRingUp * a.g_max && 4 + 8 * cap <= load;
   const bool ring_up = listed && a.d % 256 == 0;                 // stages of two k-blocks, a multiple of four of them
   const bool ring_down = listed && load >= (int64_t)kRingDown * a.g_max && a.f % 128 == 0;
   FfnArgs b = a;
